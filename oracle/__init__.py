@@ -1,0 +1,132 @@
+"""CPU oracle of the integer-only encoder layer -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes access to `qasr_oracle.cpp` (plain C++, built with g++), plus the encoder as
+"the op list applied in order".  Nothing in the product package may import this module;
+only tests, the smoke check and the benchmark's cpu_baseline leg do.  It imports nothing
+from the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "qasr_oracle.cpp")
+_LIB = os.path.join(_HERE, "libqasr_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with g++ (generic x86-64 code: the .so is also run on another box)."""
+    if force or not os.path.exists(_LIB):
+        cmd = ["g++", "-std=c++17", "-O3", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               _SRC, "-o", _LIB]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        L = ctypes.CDLL(_LIB)
+        i32, i64, u32, p = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_void_p
+        L.qasr_oracle_out_len.restype = i64
+        L.qasr_oracle_out_len.argtypes = [i64, i32, i32, i32, i32, i32]
+        L.qasr_oracle_conv1d_acc.restype = None
+        L.qasr_oracle_conv1d_acc.argtypes = [i32, i32, i32, i64, i32, i32, i32, i32, i32, i32, i64, p, p, p, p]
+        L.qasr_oracle_conv1d_int8.restype = i64
+        L.qasr_oracle_conv1d_int8.argtypes = [i32, i32, i32, i64, i32, i32, i32, i32, i32, i32, i64, i64, u32,
+                                              p, p, p, p, p, p, p]
+        L.qasr_oracle_requant.restype = None
+        L.qasr_oracle_requant.argtypes = [p, i32, i32, i64, p, p, p, p, u32, p]
+        L.qasr_oracle_requant_scalar.restype = i64
+        L.qasr_oracle_requant_scalar.argtypes = [i64, i32, i32]
+        _lib = L
+    return _lib
+
+
+def _ptr(a, dtype):
+    if a is None:
+        return None
+    assert a.dtype == dtype and a.flags["C_CONTIGUOUS"], (a.dtype, dtype)
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def out_len(Tin, k, stride=1, dilation=1, pad_left=0, pad_right=0) -> int:
+    return int(lib().qasr_oracle_out_len(Tin, k, stride, dilation, pad_left, pad_right))
+
+
+def conv1d_acc(x, w, bias=None, *, stride=1, dilation=1, pad_left=0, pad_right=0, groups=1,
+               Cin=None, x_batch_stride=0) -> np.ndarray:
+    """int64 accumulators [B,Cout,Tout] (bias included if given)."""
+    B = x.shape[0]
+    Cin = x.shape[1] if Cin is None else Cin
+    Tin = x.shape[2]
+    Cout, _, k = w.shape
+    Tout = out_len(Tin, k, stride, dilation, pad_left, pad_right)
+    acc = np.empty((B, Cout, Tout), dtype=np.int64)
+    lib().qasr_oracle_conv1d_acc(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right, groups,
+                                 x_batch_stride, _ptr(x, np.int8), _ptr(w, np.int8), _ptr(bias, np.int32),
+                                 _ptr(acc, np.int64))
+    return acc
+
+
+def conv1d_int8(x, w, bias, m, s, residual=None, *, stride=1, dilation=1, pad_left=0, pad_right=0,
+                groups=1, relu=False, Cin=None, x_batch_stride=0, check_overflow=True) -> np.ndarray:
+    """One integer layer on host arrays. x int8 [B,Cx,Tin] (Cx >= Cin when a channel-prefix
+    view is read through x_batch_stride), w int8 [Cout,Cin/groups,k], returns int8 [B,Cout,Tout]."""
+    B = x.shape[0]
+    Cin = x.shape[1] if Cin is None else Cin
+    Tin = x.shape[2]
+    Cout, _, k = w.shape
+    Tout = out_len(Tin, k, stride, dilation, pad_left, pad_right)
+    y = np.empty((B, Cout, Tout), dtype=np.int8)
+    if residual is not None:
+        assert residual.shape == y.shape
+    ovf = lib().qasr_oracle_conv1d_int8(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right, groups,
+                                        x_batch_stride, 0, 1 if relu else 0,
+                                        _ptr(x, np.int8), _ptr(w, np.int8), _ptr(bias, np.int32),
+                                        _ptr(m, np.int32), _ptr(s, np.int32), _ptr(residual, np.int8),
+                                        _ptr(y, np.int8))
+    if check_overflow and ovf:
+        raise OverflowError(f"{ovf} accumulators left the int32 range")
+    return y
+
+
+def requant(acc, bias, m, s, residual=None, relu=False) -> np.ndarray:
+    B, C, T = acc.shape
+    y = np.empty((B, C, T), dtype=np.int8)
+    lib().qasr_oracle_requant(_ptr(acc, np.int32), B, C, T, _ptr(bias, np.int32), _ptr(m, np.int32),
+                              _ptr(s, np.int32), _ptr(residual, np.int8), 1 if relu else 0, _ptr(y, np.int8))
+    return y
+
+
+def requant_scalar(A: int, m: int, s: int) -> int:
+    return int(lib().qasr_oracle_requant_scalar(A, m, s))
+
+
+def run_op(op, p, x, residual=None) -> np.ndarray:
+    """Apply one op of a network spec (fields: Cin, k, stride, ... as in the workload tables)."""
+    return conv1d_int8(x, p["w"], p["bias"], p["m"], p["s"], residual, stride=op.stride,
+                       dilation=op.dilation, pad_left=op.pad_left, pad_right=op.pad_right,
+                       groups=op.groups, relu=bool(op.flags & 1), Cin=op.Cin,
+                       x_batch_stride=op.x_batch_stride)
+
+
+def encoder_forward(net, params, x, keep=False):
+    """The op list applied in order over activation slots; returns the last op's output
+    (and every op's output when keep=True)."""
+    slots = {0: x}
+    outs = []
+    for op, p in zip(net.ops, params):
+        xin = slots[op.in_slot]
+        res = slots[op.res_slot] if op.res_slot >= 0 else None
+        y = run_op(op, p, xin, res)
+        slots[op.out_slot] = y
+        if keep:
+            outs.append(y)
+    return (y, outs) if keep else y

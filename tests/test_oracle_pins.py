@@ -1,0 +1,312 @@
+"""Pins for the CPU oracle against things other than itself (CPU only).
+
+The paper prints no worked numeric example of the integer pipeline, so the oracle is pinned
+by: arbitrary-precision brute force on tiny shapes (a definition written differently: explicit
+zero-padded signals and exact rational rounding), a float64 library convolution at real
+shapes (exact below 2^53), closed forms, the (2^30, 30) identity, hand-worked rounding and
+saturation vectors (tests/golden/requant_vectors.txt) and the float product within 1 LSB
+(linearity of Sec. 2.2).
+"""
+import itertools
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import qasr_workloads as W
+from qasr_workloads.rng import randint_array
+
+
+# ----------------------------------------------------------------------------- big-int model
+def py_round_half_up(fr: Fraction) -> int:
+    return math.floor(fr + Fraction(1, 2))
+
+
+def py_layer(x, w, bias, m, s, residual, stride, dil, pl, pr, depthwise, relu, Cin=None):
+    """Nested Python lists, exact ints / rationals.  The conv is written over an explicitly
+    zero-padded signal so that it does not share the oracle's index arithmetic."""
+    B = len(x)
+    Cin = len(x[0]) if Cin is None else Cin
+    Tin = len(x[0][0])
+    Cout, k = len(w), len(w[0][0])
+    y = []
+    for b in range(B):
+        padded = [[0] * pl + [int(v) for v in x[b][c]] + [0] * pr for c in range(Cin)]
+        L = Tin + pl + pr
+        yb = []
+        for co in range(Cout):
+            row = []
+            to = 0
+            while to * stride + dil * (k - 1) < L:
+                start = to * stride
+                chans = [co] if depthwise else range(Cin)
+                A = int(bias[co]) if bias is not None else 0
+                for idx, ci in enumerate(chans):
+                    taps = w[co][0] if depthwise else w[co][ci]
+                    A += sum(int(taps[j]) * padded[ci][start + j * dil] for j in range(k))
+                v = py_round_half_up(Fraction(A * int(m[co]), 2 ** int(s[co])))
+                if residual is not None:
+                    v += int(residual[b][co][to])
+                row.append(min(127, max(0 if relu else -128, v)))
+                to += 1
+            yb.append(row)
+        y.append(yb)
+    return y
+
+
+def _draw(seed, shape, lo, hi, dtype):
+    return randint_array(seed, shape, lo, hi, dtype)
+
+
+# ----------------------------------------------------------------------------- a2-a8 brute force
+GEOMS = [(k, stride, dil, pl, pr) for k in (1, 2, 3, 5) for stride in (1, 2) for dil in (1, 2)
+         for (pl, pr) in ((0, 0), (2, 1), (dil * (k - 1) // 2, dil * (k - 1) - dil * (k - 1) // 2))]
+
+
+@pytest.mark.parametrize("depthwise", [False, True])
+def test_brute_force_tiny_layers(depthwise):
+    n = 0
+    for gi, (k, stride, dil, pl, pr) in enumerate(GEOMS):
+        for (B, Cin, Cout, T) in ((1, 1, 1, 9), (2, 3, 5, 17), (1, 8, 8, 12)):
+            if depthwise:
+                Cout = Cin
+            if T + pl + pr < dil * (k - 1) + 1:
+                continue
+            sd = 1000 * gi + 10 * Cin + T + (5 if depthwise else 0)
+            x = _draw(sd, (B, Cin, T), -128, 127, np.int8)
+            w = _draw(sd + 1, (Cout, 1 if depthwise else Cin, k), -128, 127, np.int8)
+            bias = _draw(sd + 2, (Cout,), -300, 300, np.int32) if gi % 3 else None
+            # small scales so that outputs are neither all saturated nor all zero
+            m = _draw(sd + 3, (Cout,), 1 << 30, (1 << 31) - 1, np.int32)
+            s = _draw(sd + 4, (Cout,), 36, 42, np.int32)
+            Tout = oracle.out_len(T, k, stride, dil, pl, pr)
+            res = _draw(sd + 5, (B, Cout, Tout), -128, 127, np.int8) if gi % 2 else None
+            relu = bool(gi % 4 < 2)
+            got = oracle.conv1d_int8(x, w, bias, m, s, res, stride=stride, dilation=dil, pad_left=pl,
+                                     pad_right=pr, groups=Cin if depthwise else 1, relu=relu)
+            ref = py_layer(x.tolist(), w.tolist(), None if bias is None else bias.tolist(), m.tolist(),
+                           s.tolist(), None if res is None else res.tolist(), stride, dil, pl, pr,
+                           depthwise, relu)
+            assert got.shape == (B, Cout, Tout)
+            assert got.tolist() == ref, (k, stride, dil, pl, pr, B, Cin, Cout, T)
+            n += 1
+    assert n > 100
+
+
+def test_brute_force_is_not_vacuous():
+    """The scales above give a spread of outputs (not all 0 / saturated)."""
+    x = _draw(7, (2, 8, 40), -128, 127, np.int8)
+    w = _draw(8, (8, 8, 5), -127, 127, np.int8)
+    m = _draw(9, (8,), 1 << 30, (1 << 31) - 1, np.int32)
+    s = np.full(8, 38, np.int32)
+    y = oracle.conv1d_int8(x, w, None, m, s, pad_left=2, pad_right=2)
+    vals = set(y.reshape(-1).tolist())
+    assert len(vals) > 50
+
+
+# ----------------------------------------------------------------------------- library routine at real shapes
+@pytest.mark.parametrize("Cin,Cout,T,k,stride,dil,groups", [
+    (64, 256, 400, 33, 2, 1, 1),      # C1-like dense, stride 2
+    (256, 256, 200, 33, 1, 1, 256),   # config-0 depthwise
+    (256, 256, 200, 1, 1, 1, 1),      # config-0 pointwise
+    (512, 512, 300, 87, 1, 2, 512),   # C2-like depthwise, dilation 2
+    (96, 80, 150, 29, 1, 2, 1),       # Jasper-epilogue-like dense, dilation 2
+    (512, 512, 100, 32, 1, 1, 512),   # even kernel, asymmetric pad
+])
+def test_accumulators_equal_float64_library_conv(Cin, Cout, T, k, stride, dil, groups):
+    tot = dil * (k - 1)
+    pl, pr = tot // 2, tot - tot // 2
+    x = _draw(11, (2, Cin, T), -128, 127, np.int8)
+    w = _draw(12, (Cout, 1 if groups != 1 else Cin, k), -128, 127, np.int8)
+    bias = _draw(13, (Cout,), -(1 << 16), 1 << 16, np.int32)
+    acc = oracle.conv1d_acc(x, w, bias, stride=stride, dilation=dil, pad_left=pl, pad_right=pr, groups=groups)
+    xt = torch.nn.functional.pad(torch.from_numpy(x).double(), (pl, pr))
+    ref = torch.nn.functional.conv1d(xt, torch.from_numpy(w).double(), torch.from_numpy(bias).double(),
+                                     stride=stride, dilation=dil, groups=groups)
+    assert ref.abs().max() < 2 ** 52
+    assert np.array_equal(acc, ref.numpy().astype(np.int64))
+
+
+# ----------------------------------------------------------------------------- closed forms
+def _identity_scale(C):
+    return np.full(C, 1 << 30, np.int32), np.full(C, 30, np.int32)
+
+
+def test_one_hot_tap_shifts_the_input():
+    C, T, k = 3, 20, 7
+    x = _draw(21, (1, C, T), -128, 127, np.int8)
+    m, s = _identity_scale(C)
+    for j in range(k):
+        w = np.zeros((C, 1, k), np.int8)
+        w[:, 0, j] = 1
+        y = oracle.conv1d_int8(x, w, None, m, s, pad_left=3, pad_right=3, groups=C)
+        shift = j - 3                       # y[t] = x[t + shift], zeros outside
+        ref = np.zeros_like(x)
+        for t in range(T):
+            if 0 <= t + shift < T:
+                ref[0, :, t] = x[0, :, t + shift]
+        assert np.array_equal(y, ref)
+
+
+def test_identity_pointwise_and_channel_sum():
+    C, T = 6, 15
+    x = _draw(22, (2, C, T), -128, 127, np.int8)
+    m, s = _identity_scale(C)
+    eye = np.eye(C, dtype=np.int8).reshape(C, C, 1)
+    assert np.array_equal(oracle.conv1d_int8(x, eye, None, m, s), x)
+    ones = np.ones((1, C, 1), np.int8)
+    acc = oracle.conv1d_acc(x, ones)
+    assert np.array_equal(acc[:, 0, :], x.astype(np.int64).sum(axis=1))
+
+
+def test_weight_order_is_cout_cin_k_and_no_flip():
+    """A transposed weight operand or a flipped kernel must fail: single non-zero weight."""
+    Cin, Cout, T, k = 3, 4, 10, 3
+    x = _draw(23, (1, Cin, T), -128, 127, np.int8)
+    w = np.zeros((Cout, Cin, k), np.int8)
+    w[2, 1, 0] = 1                           # out-channel 2 reads in-channel 1 at tap 0
+    acc = oracle.conv1d_acc(x, w, pad_left=0, pad_right=0)
+    assert acc.shape == (1, Cout, T - 2)
+    assert np.array_equal(acc[0, 2], x[0, 1, :T - 2].astype(np.int64))
+    assert not acc[0, [0, 1, 3]].any()
+
+
+def test_linearity_in_the_weights():
+    x = _draw(24, (1, 5, 30), -128, 127, np.int8)
+    w1 = _draw(25, (4, 5, 3), -60, 60, np.int8)
+    w2 = _draw(26, (4, 5, 3), -60, 60, np.int8)
+    a = oracle.conv1d_acc(x, w1, pad_left=1, pad_right=1)
+    b = oracle.conv1d_acc(x, w2, pad_left=1, pad_right=1)
+    c = oracle.conv1d_acc(x, (w1 + w2).astype(np.int8), pad_left=1, pad_right=1)
+    assert np.array_equal(a + b, c)
+
+
+def test_channel_prefix_view_reads_first_cin_channels():
+    x = _draw(27, (2, 8, 9), -128, 127, np.int8)
+    w = _draw(28, (4, 1, 4), -127, 127, np.int8)
+    m, s = _identity_scale(4)
+    s[:] = 36
+    full = oracle.conv1d_int8(x, w, None, m, s, pad_left=1, pad_right=2, groups=4, Cin=4, x_batch_stride=8 * 9)
+    sliced = oracle.conv1d_int8(np.ascontiguousarray(x[:, :4]), w, None, m, s, pad_left=1, pad_right=2, groups=4)
+    assert np.array_equal(full, sliced)
+
+
+# ----------------------------------------------------------------------------- a6 requant
+def test_identity_requant_on_int32_edges_and_samples():
+    edges = [-(1 << 31), -(1 << 31) + 1, -129, -128, -1, 0, 1, 127, 128, (1 << 31) - 2, (1 << 31) - 1]
+    rnd = [int(v) for v in _draw(31, (2000,), -(1 << 31), (1 << 31) - 1, np.int64)]
+    for A in edges + rnd:
+        assert oracle.requant_scalar(A, 1 << 30, 30) == A
+
+
+def test_hand_worked_vectors(golden):
+    rows = golden("requant_vectors.txt")
+    assert len(rows) >= 24
+    for A, m, s, v, y, yr in (map(int, r) for r in rows):
+        assert oracle.requant_scalar(A, m, s) == v, (A, m, s)
+        acc = np.array([[[A]]], np.int32)
+        mm, ss = np.array([m], np.int32), np.array([s], np.int32)
+        assert oracle.requant(acc, None, mm, ss).item() == y
+        assert oracle.requant(acc, None, mm, ss, relu=True).item() == yr
+
+
+def test_requant_equals_exact_rational_rounding_everywhere():
+    rnd = np.random.RandomState(5)
+    cases = [(A, m, s) for A in (-(1 << 31), -1, 0, 1, (1 << 31) - 1)
+             for m in (0, 1, 1 << 30, (1 << 31) - 1) for s in (1, 2, 30, 31, 32, 33, 44, 62)]
+    for _ in range(3000):
+        cases.append((int(rnd.randint(-(1 << 31), 1 << 31)), int(rnd.randint(0, 1 << 31)), int(rnd.randint(1, 63))))
+    for A, m, s in cases:
+        assert oracle.requant_scalar(A, m, s) == py_round_half_up(Fraction(A * m, 1 << s)), (A, m, s)
+
+
+def test_float_dequantised_product_within_one_lsb():
+    """Sec. 2.2: S_W S_x Conv(q_W, q_x); the dyadic pair (m, s) stands for the real scale
+    m / 2^s, so the float product must agree with the integer rescale to within 1 LSB, and
+    exactly when the product is not within 1e-6 of a tie."""
+    rnd = np.random.RandomState(6)
+    A = rnd.randint(-(1 << 28), 1 << 28, size=20000).astype(np.int64)
+    m = rnd.randint(1 << 30, 1 << 31, size=20000).astype(np.int64)
+    s = rnd.randint(36, 45, size=20000).astype(np.int64)
+    f = A.astype(np.float64) * (m.astype(np.float64) / np.exp2(s.astype(np.float64)))
+    fr = np.floor(f + 0.5)
+    got = np.array([oracle.requant_scalar(int(a), int(mm), int(ss)) for a, mm, ss in zip(A, m, s)], np.float64)
+    assert np.abs(got - fr).max() <= 1
+    far = np.abs((f + 0.5) - np.round(f + 0.5)) > 1e-6
+    assert far.mean() > 0.99 and np.array_equal(got[far], fr[far])
+
+
+# ----------------------------------------------------------------------------- a7, a8 residual + clamp
+def test_residual_is_added_before_the_single_clamp():
+    """rq = 200 (beyond int8), r = -100  =>  100, not clamp(127 - 100) = 27."""
+    acc = np.array([[[200, 200, -300, 50]]], np.int32)
+    r = np.array([[[-100, 100, 127, -128]]], np.int8)
+    m, s = _identity_scale(1)
+    assert oracle.requant(acc, None, m, s, r).reshape(-1).tolist() == [100, 127, -128, -78]
+    assert oracle.requant(acc, None, m, s, r, relu=True).reshape(-1).tolist() == [100, 127, 0, 0]
+
+
+def test_bias_is_added_before_the_rescale():
+    acc = np.array([[[3], [3]]], np.int32)
+    bias = np.array([1, -1], np.int32)
+    m, s = np.full(2, 1 << 30, np.int32), np.full(2, 31, np.int32)     # halve, ties up
+    assert oracle.requant(acc, bias, m, s).reshape(-1).tolist() == [2, 1]
+
+
+def test_per_channel_scales_are_indexed_by_output_channel():
+    x = np.full((1, 2, 4), 64, np.int8)
+    w = np.zeros((3, 2, 1), np.int8)
+    w[:, 0, 0] = 1
+    m = np.full(3, 1 << 30, np.int32)
+    s = np.array([30, 31, 32], np.int32)
+    y = oracle.conv1d_int8(x, w, None, m, s)
+    assert y[0, :, 0].tolist() == [64, 32, 16]
+
+
+def test_overflow_is_detected():
+    Cin, k = 2200, 64                      # fan-in 140800 * 128 * 128 > 2^31
+    x = np.full((1, Cin, k), -128, np.int8)
+    w = np.full((1, Cin, k), -128, np.int8)
+    m, s = _identity_scale(1)
+    with pytest.raises(OverflowError):
+        oracle.conv1d_int8(x, w, None, m, s)
+
+
+# ----------------------------------------------------------------------------- a9 wiring on tiny encoders
+def py_encoder(net, params, x):
+    slots = {0: x.tolist()}
+    for op, p in zip(net.ops, params):
+        res = slots[op.res_slot] if op.res_slot >= 0 else None
+        slots[op.out_slot] = py_layer(
+            slots[op.in_slot], p["w"].tolist(), None if p["bias"] is None else p["bias"].tolist(),
+            p["m"].tolist(), p["s"].tolist(), res, op.stride, op.dilation, op.pad_left, op.pad_right,
+            op.depthwise, bool(op.flags & 1), Cin=op.Cin)
+    return slots[net.ops[-1].out_slot]
+
+
+@pytest.mark.parametrize("cfg", range(5))
+def test_tiny_encoders_match_big_int_composition(cfg):
+    net = W.tiny_config(cfg)
+    for seed in (1, 2):
+        # scales chosen for the tiny fan-in so that layers neither saturate nor vanish
+        params = W.draw_net_params(net, seed, s_lo=37, s_hi=38, bias_mag=300)
+        x = W.draw_input(net, seed)
+        y, outs = oracle.encoder_forward(net, params, x, keep=True)
+        assert y.tolist() == py_encoder(net, params, x)
+        assert y.shape == (net.B, net.Cout, net.Tout)
+        live = [len(set(o.reshape(-1).tolist())) for o in outs]
+        assert min(live) >= 5, live        # no layer collapsed to a constant
+
+
+def test_config0_oracle_is_not_degenerate():
+    net = W.build_config(0)
+    params = W.draw_net_params(net, 1)
+    x = W.draw_input(net, 1)
+    y, outs = oracle.encoder_forward(net, params, x, keep=True)
+    for o in outs:
+        flat = o.reshape(-1)
+        sat = np.mean((flat == 127) | (flat == -128))
+        assert 0.02 < sat < 0.98 and len(set(flat.tolist())) > 100

@@ -1,0 +1,115 @@
+"""Pins for the seeded input generator and the network shape tables (CPU only)."""
+import numpy as np
+import pytest
+
+import qasr_workloads as W
+from qasr_workloads.rng import splitmix64_scalar, splitmix64_stream, randint_array, tensor_seed
+
+
+def test_splitmix64_matches_public_test_vector(golden):
+    ref = [int(r[0]) for r in golden("splitmix64_seed1234567.txt")]
+    assert splitmix64_scalar(1234567, 5) == ref
+    assert [int(v) for v in splitmix64_stream(1234567, 5)] == ref
+
+
+def test_vectorised_stream_equals_scalar_stream():
+    for seed in (0, 1, 2**63 + 12345, 2**64 - 1):
+        a = [int(v) for v in splitmix64_stream(seed, 257)]
+        assert a == splitmix64_scalar(seed, 257)
+        b = [int(v) for v in splitmix64_stream(seed, 50, offset=207)]
+        assert b == a[207:]
+
+
+def test_randint_is_lo_plus_mod_span_and_chunking_is_invisible():
+    seed = tensor_seed(1, 0, 0, "w")
+    ref = [(-127 + (u % 255)) for u in splitmix64_scalar(seed, 1000)]
+    got = randint_array(seed, (10, 100), -127, 127, np.int8)
+    assert got.dtype == np.int8 and got.reshape(-1).tolist() == ref
+    m = randint_array(seed, (64,), 1 << 30, (1 << 31) - 1, np.int32)
+    assert m.min() >= 1 << 30 and m.max() < 1 << 31
+    s = randint_array(seed, (4096,), 36, 44, np.int32)
+    assert set(s.tolist()) == set(range(36, 45))
+
+
+def test_tensor_seeds_are_distinct():
+    seen = {tensor_seed(b, c, o, k) for b in (1, 2, 3) for c in range(5) for o in range(-1, 40)
+            for k in ("x", "w", "bias", "m", "s")}
+    assert len(seen) == 3 * 5 * 41 * 5
+
+
+@pytest.mark.parametrize("cfg,n_ops,n_dw,macs_g,weights_m,out_shape", [
+    (0, 2, 1, 0.0148, 0.074, (1, 256, 200)),
+    (1, 60, 26, 5.77, 7.21, (1, 29, 800)),
+    (2, 170, 76, 495.9, 19.37, (32, 29, 800)),
+    (3, 64, 0, 4124.0, 322.2, (16, 29, 800)),
+    (4, 85, 17, 315.5, 49.3, (16, 512, 400)),
+])
+def test_config_shapes(cfg, n_ops, n_dw, macs_g, weights_m, out_shape):
+    net = W.build_config(cfg)
+    assert len(net.ops) == n_ops
+    assert sum(o.depthwise for o in net.ops) == n_dw
+    assert W.net_macs(net) / 1e9 == pytest.approx(macs_g, rel=2e-3)
+    assert W.net_weight_count(net) / 1e6 == pytest.approx(weights_m, rel=2e-3)
+    assert (net.B, net.Cout, net.Tout) == out_shape
+    # int32 accumulators cannot overflow at these shapes: fan_in * 128 * 127 + 2^16 < 2^31
+    for o in net.ops:
+        fan = o.k if o.depthwise else o.Cin * o.k
+        assert fan * 128 * 127 + (1 << 16) < (1 << 31)
+
+
+def test_networks_agree_with_paper_table1_size_and_bops(golden):
+    tab = {r[0]: (float(r[1]), float(r[2])) for r in golden("table1_size_bops.txt")}
+    # 10 s at 16 kHz with a 10 ms hop = 1000 feature frames, batch 1
+    q = W.quartznet(1, 1000, 3, config_id=2)
+    j = W.jasper(1, 1000, config_id=3)
+    for net, key in ((q, "quartznet"), (j, "jasper")):
+        size_mb, bops_t = tab[key]
+        assert W.net_weight_count(net) / 1e6 == pytest.approx(size_mb, rel=0.10)
+        assert W.net_macs(net) * 64 / 1e12 == pytest.approx(bops_t, rel=0.10)
+
+
+@pytest.mark.parametrize("cfg", range(5))
+def test_slot_wiring_is_hazard_free(cfg):
+    """No op writes a slot it reads, slot 0 is never written, and every read slot holds the
+    tensor the builder meant (replay with symbolic tensor ids)."""
+    for net in (W.build_config(cfg), W.tiny_config(cfg)):
+        holds = {0: ("x", net.Cin, net.Tin)}
+        for i, o in enumerate(net.ops):
+            assert o.out_slot != 0 and o.out_slot != o.in_slot and o.out_slot != o.res_slot
+            assert o.in_slot in holds
+            _, c_in, t_in = holds[o.in_slot]
+            assert t_in == o.Tin and c_in >= o.Cin
+            if o.x_batch_stride:
+                assert o.x_batch_stride == c_in * t_in
+            else:
+                assert c_in == o.Cin
+            if o.res_slot >= 0:
+                assert holds[o.res_slot][1:] == (o.Cout, o.Tout)
+                assert holds[o.res_slot][0].endswith(".res")
+            holds[o.out_slot] = (o.name, o.Cout, o.Tout)
+            assert max(o.in_slot, o.res_slot, o.out_slot) < net.n_slots
+
+
+def test_quartznet_block_structure():
+    net = W.build_config(1)
+    names = [o.name for o in net.ops]
+    assert names[0] == "C1" and names[-3:] == ["C2.pw", "C3", "C4"]
+    blk = net.ops[1:12]
+    assert blk[0].name == "B1.0.res" and not blk[0].flags & 1
+    assert [o.depthwise for o in blk[1:]] == [True, False] * 5
+    assert all(o.res_slot < 0 for o in blk[:-1]) and blk[-1].res_slot == blk[0].out_slot
+    assert all(not o.has_bias and not (o.flags & 1) for o in blk[1::2])     # depthwise: no bias, no ReLU
+    assert all(o.has_bias and (o.flags & 1) for o in blk[2::2])            # pointwise: bias + ReLU
+    b3 = [o for o in net.ops if o.name.startswith("B3.0")]
+    assert (b3[0].Cin, b3[0].Cout) == (256, 512) and (b3[1].Cin, b3[1].k) == (256, 51)
+    assert (b3[2].Cin, b3[2].Cout) == (256, 512)
+    c2 = net.ops[-4]
+    assert (c2.k, c2.dilation, c2.pad_left, c2.pad_right, c2.Tout) == (87, 2, 86, 86, 800)
+    assert not net.ops[-1].flags & 1
+
+
+def test_conformer_even_kernel_padding_and_view():
+    net = W.build_config(4)
+    dw = net.ops[3]
+    assert (dw.k, dw.pad_left, dw.pad_right, dw.Tout) == (32, 15, 16, 400)
+    assert dw.Cin == 512 and dw.x_batch_stride == 1024 * 400
