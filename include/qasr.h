@@ -1,0 +1,173 @@
+/* qasr.h -- C ABI of the integer-only ASR encoder library for AMD MI355X (gfx950).
+ *
+ * The library executes the INT8 inference path of "Integer-only Zero-shot Quantization for
+ * Efficient Speech Recognition" (arXiv 2103.16827): every layer is an integer convolution
+ * applied directly to the quantised values (Sec. 2.2), with BatchNorm folded into the
+ * preceding convolution (Sec. 2.2; at run time an int32 bias), followed by a static
+ * per-channel dyadic rescale back to int8 (Sec. 2.1: static quantisation, all scales are
+ * inference-time constants), integer ReLU (Sec. 2.2) and an integer residual add.
+ *
+ * One layer, for b in [0,B), co in [0,Cout), to in [0,Tout):
+ *
+ *     A  = bias ? bias[co] : 0                                          (int32)
+ *     A += sum_{ci, j} x[b, ci, to*stride - pad_left + j*dilation] * w[co, ci', j]
+ *                      (terms whose time index falls outside [0,Tin) are 0: symmetric
+ *                       quantisation has zero-point 0, Eq. 1; cross-correlation, no flip;
+ *                       groups == 1: ci over [0,Cin), ci' = ci;
+ *                       depthwise (groups == Cin == Cout): ci = co, ci' = 0)
+ *     v  = floor((A * m[co] + 2^(s[co]-1)) / 2^s[co])                   (round half up)
+ *     v += residual ? residual[b, co, to] : 0
+ *     y[b, co, to] = clamp(v, (flags & QASR_FLAG_RELU) ? 0 : -128, 127)
+ *
+ * Conventions
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller (allocate through any HIP
+ *    allocator, e.g. PyTorch-ROCm).  Descriptors, op lists and handles are HOST memory.
+ *  - Layout: activations int8 [B, C, T] with T contiguous; weights int8 [Cout, Cin/groups, k]
+ *    (PyTorch Conv1d order); bias, m, s int32 [Cout].
+ *  - Forward calls only enqueue work on `stream` (a hipStream_t, NULL = default stream) and
+ *    return; they never allocate device memory and never synchronise.
+ *  - All argument validation happens before the first HIP call, so error paths can be
+ *    exercised without a GPU.  Errors are returned as qasr_status; nothing throws or aborts.
+ *  - Per-channel constants must satisfy 0 <= m < 2^31 and 1 <= s <= 62; they live in device
+ *    memory and are not checked by forward calls (out-of-range values give undefined output
+ *    values, never out-of-bounds accesses).
+ *  - The int32 accumulator wraps on overflow; the caller guarantees
+ *    fan_in * 128 * 128 + |bias| < 2^31.
+ *  - y must not overlap x or residual.
+ */
+#ifndef QASR_H_
+#define QASR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  QASR_OK = 0,
+  QASR_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  QASR_ERR_SHAPE = -2,       /* a size is < 1, Tout < 1, or a stride is too small           */
+  QASR_ERR_PARAM = -3,       /* unknown flag bits, bad slot index, bad op wiring            */
+  QASR_ERR_UNSUPPORTED = -4, /* groups not in {1, Cin==Cout}                                */
+  QASR_ERR_ALIAS = -5,       /* y overlaps x or residual                                    */
+  QASR_ERR_WORKSPACE = -6,   /* workspace NULL, misaligned or too small                     */
+  QASR_ERR_HIP = -7          /* a HIP runtime call or kernel launch failed                  */
+} qasr_status;
+
+enum {
+  QASR_FLAG_RELU = 1u,     /* clamp to [0,127] instead of [-128,127] (integer ReLU, Sec. 2.2)        */
+  QASR_FLAG_W_PACKED = 2u  /* `w` was produced by qasr_pack_weights for this descriptor              */
+};
+
+typedef struct {
+  int32_t B, Cin, Cout, Tin;               /* >= 1; Tout is derived (qasr_conv1d_out_len)             */
+  int32_t k, stride, dilation;             /* >= 1                                                    */
+  int32_t pad_left, pad_right;             /* >= 0, implicit zeros                                    */
+  int32_t groups;                          /* 1 = dense / pointwise; == Cin == Cout = depthwise       */
+  int64_t x_batch_stride, y_batch_stride;  /* elements between batch items; 0 => C*T.  A larger
+                                              x stride lets a layer read a channel-prefix view.
+                                              The residual tensor uses y_batch_stride as well.        */
+  uint32_t flags;                          /* QASR_FLAG_*                                             */
+} qasr_conv1d_desc;
+
+/* Tout = floor((Tin + pad_left + pad_right - dilation*(k-1) - 1) / stride) + 1, or a negative
+ * qasr_status if the descriptor is invalid (NULL, sizes < 1, or no output frame). */
+int32_t qasr_conv1d_out_len(const qasr_conv1d_desc* d);
+
+/* One integer layer as defined at the top of this file (Sec. 2.2: integer convolution, folded
+ * BatchNorm bias, integer ReLU; dyadic rescale and residual as stated above).
+ *   x        [B,Cin,Tin]  int8 device (batch stride x_batch_stride)
+ *   w        [Cout,Cin/groups,k] int8 device; with QASR_FLAG_W_PACKED the buffer written by
+ *            qasr_pack_weights (only meaningful for groups == 1 and k > 1; otherwise the
+ *            packed form is the plain form)
+ *   bias     [Cout] int32 device, or NULL for 0
+ *   m, s     [Cout] int32 device
+ *   residual [B,Cout,Tout] int8 device or NULL
+ *   y        [B,Cout,Tout] int8 device (batch stride y_batch_stride)
+ * Dense convolutions with k > 1 run fastest with packed weights; with plain weights a slower
+ * kernel is used.  Asynchronous on `stream`. */
+qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const int8_t* w,
+                             const int32_t* bias, const int32_t* m, const int32_t* s,
+                             const int8_t* residual, int8_t* y, void* stream);
+
+/* Size in bytes of the packed form of a layer's weights (0 on an invalid descriptor). */
+size_t qasr_packed_weight_bytes(const qasr_conv1d_desc* d);
+
+/* Re-orders w [Cout,Cin,k] into the tap-major form [k][Cout][Cin] that the implicit-GEMM
+ * kernel consumes with 16-byte operand loads.  Weights are fixed at inference (Sec. 2.1,
+ * static quantisation), so this runs once per layer.  w_packed: device, caller-owned,
+ * qasr_packed_weight_bytes(d) bytes, 16-byte aligned.  Asynchronous on `stream`. */
+qasr_status qasr_pack_weights(const qasr_conv1d_desc* d, const int8_t* w, int8_t* w_packed,
+                              void* stream);
+
+/* The layer epilogue alone (bias, dyadic rescale, residual, clamp) on int32 accumulators:
+ *   acc [B,C,T] int32 device; bias/m/s [C]; residual, y [B,C,T] int8 device (contiguous).
+ * flags: QASR_FLAG_RELU only.  Asynchronous on `stream`. */
+qasr_status qasr_requant(const int32_t* acc, int32_t B, int32_t C, int32_t T,
+                         const int32_t* bias, const int32_t* m, const int32_t* s,
+                         const int8_t* residual, uint32_t flags, int8_t* y, void* stream);
+
+/* An encoder is a flat list of layers over numbered activation slots (the evaluated models of
+ * Sec. 3 are such lists: QuartzNet, Jasper, Conformer-shaped linear layers).  Slot 0 is the
+ * network input `x`; the last op's out_slot is the network output `y`; every other slot
+ * lives in the caller's workspace. */
+typedef struct {
+  qasr_conv1d_desc d;        /* d.x_batch_stride / y_batch_stride as for qasr_conv1d_int8; flags
+                                must not contain QASR_FLAG_W_PACKED (create packs by itself)         */
+  const int8_t* w;           /* device, plain order; must stay valid while the encoder lives        */
+  const int32_t* bias;       /* device or NULL                                                      */
+  const int32_t* m;          /* device                                                              */
+  const int32_t* s;          /* device                                                              */
+  int32_t in_slot;           /* slot read                                                           */
+  int32_t res_slot;          /* slot added in the epilogue, or -1                                   */
+  int32_t out_slot;          /* slot written; != in_slot, != res_slot, != 0                         */
+} qasr_op;
+
+typedef struct qasr_encoder qasr_encoder; /* opaque host object */
+
+/* Validates the op list (shapes chain through the slots, no op writes a slot it reads, slot 0
+ * is never written), sizes the slots, and packs dense k > 1 weights once into device memory
+ * owned by the encoder (the only device allocation the library ever makes; it synchronises
+ * `stream`-independent, i.e. it blocks until packing is done).  *out is set on QASR_OK. */
+qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slots,
+                                qasr_encoder** out);
+
+/* Bytes of workspace qasr_encoder_forward needs (all slots except the input and the output,
+ * each rounded up to 256 bytes). */
+size_t qasr_encoder_workspace_bytes(const qasr_encoder* e);
+
+/* Runs every op in order on `stream`.  x: [B,Cin,Tin] of the first op's descriptor; y: output
+ * of the last op; workspace: device, 256-byte aligned, >= qasr_encoder_workspace_bytes(e).
+ * Enqueues n_ops kernels and returns; allocates nothing; may be captured into a HIP graph. */
+qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same as qasr_encoder_forward, but brackets every op with HIP events, waits for completion and
+ * writes each op's device time in milliseconds to op_ms[0..n_ops) (HOST memory).  For
+ * profiling only: it synchronises and creates/destroys events. */
+qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, int8_t* y,
+                                       void* workspace, size_t workspace_bytes, void* stream,
+                                       float* op_ms);
+
+/* Number of ops, and the name of the kernel family op i is dispatched to ("dw_mfma",
+ * "gemm_mfma", "conv_generic", ...; static storage, NULL if i is out of range). */
+int32_t qasr_encoder_num_ops(const qasr_encoder* e);
+const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i);
+
+void qasr_encoder_destroy(qasr_encoder* e);
+
+/* Name of the kernel family qasr_conv1d_int8 would dispatch this descriptor to (host-only). */
+const char* qasr_conv1d_kernel_name(const qasr_conv1d_desc* d);
+
+const char* qasr_status_string(qasr_status st);
+
+/* Name of the HIP error behind the calling thread's most recent QASR_ERR_HIP ("hipSuccess" if
+ * there was none).  Static storage. */
+const char* qasr_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QASR_H_ */

@@ -34,6 +34,8 @@ def lib():
         build(force=False)
         L = ctypes.CDLL(_LIB)
         i32, i64, u32, p = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_void_p
+        L.qasr_oracle_num_threads.restype = i32
+        L.qasr_oracle_num_threads.argtypes = []
         L.qasr_oracle_out_len.restype = i64
         L.qasr_oracle_out_len.argtypes = [i64, i32, i32, i32, i32, i32]
         L.qasr_oracle_conv1d_acc.restype = None
@@ -54,6 +56,10 @@ def _ptr(a, dtype):
         return None
     assert a.dtype == dtype and a.flags["C_CONTIGUOUS"], (a.dtype, dtype)
     return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def num_threads() -> int:
+    return int(lib().qasr_oracle_num_threads())
 
 
 def out_len(Tin, k, stride=1, dilation=1, pad_left=0, pad_right=0) -> int:

@@ -24,6 +24,9 @@
 // are pinned by composition only.
 #include <cstdint>
 #include <cstddef>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 namespace {
 
@@ -75,6 +78,15 @@ inline int64_t acc_one(const int8_t* xb /* batch item base */, const int8_t* w, 
 }  // namespace
 
 extern "C" {
+
+// Threads the OpenMP loops will use (1 when built without OpenMP).
+int qasr_oracle_num_threads() {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 int64_t qasr_oracle_out_len(int64_t Tin, int k, int stride, int dil, int pl, int pr) {
     return out_len(Tin, k, stride, dil, pl, pr);

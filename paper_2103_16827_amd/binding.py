@@ -1,0 +1,188 @@
+"""ctypes binding of libqasr.so: same names as the C ABI, marshalling only.
+
+Tensors are torch tensors on the GPU (PyTorch is used for device memory and streams only);
+the binding passes `data_ptr()` and the current stream to the library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqasr.so")
+
+FLAG_RELU = 1
+FLAG_W_PACKED = 2
+
+_i32, _i64, _u32, _vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_void_p
+
+
+class ConvDesc(ctypes.Structure):
+    """Mirror of qasr_conv1d_desc."""
+    _fields_ = [("B", _i32), ("Cin", _i32), ("Cout", _i32), ("Tin", _i32),
+                ("k", _i32), ("stride", _i32), ("dilation", _i32),
+                ("pad_left", _i32), ("pad_right", _i32), ("groups", _i32),
+                ("x_batch_stride", _i64), ("y_batch_stride", _i64), ("flags", _u32)]
+
+
+class _Op(ctypes.Structure):
+    """Mirror of qasr_op."""
+    _fields_ = [("d", ConvDesc), ("w", _vp), ("bias", _vp), ("m", _vp), ("s", _vp),
+                ("in_slot", _i32), ("res_slot", _i32), ("out_slot", _i32)]
+
+
+class QasrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = f" [{lib().qasr_last_hip_error().decode()}]" if status == -7 else ""
+        super().__init__(f"{where}: {status_string(status)} ({status}){detail}")
+
+
+_lib = None
+
+
+def lib():
+    """Loads the built library; raises if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # PyTorch ships its own HIP runtime; it has to be in the process before this library is
+        # loaded so that both resolve to the same runtime instance (two instances cannot share
+        # the device, streams or allocations).
+        import torch  # noqa: F401
+        L = ctypes.CDLL(LIB_PATH)
+        dp = ctypes.POINTER(ConvDesc)
+        L.qasr_conv1d_out_len.restype = _i32
+        L.qasr_conv1d_out_len.argtypes = [dp]
+        L.qasr_conv1d_int8.restype = _i32
+        L.qasr_conv1d_int8.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.qasr_packed_weight_bytes.restype = ctypes.c_size_t
+        L.qasr_packed_weight_bytes.argtypes = [dp]
+        L.qasr_pack_weights.restype = _i32
+        L.qasr_pack_weights.argtypes = [dp, _vp, _vp, _vp]
+        L.qasr_requant.restype = _i32
+        L.qasr_requant.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _u32, _vp, _vp]
+        L.qasr_encoder_create.restype = _i32
+        L.qasr_encoder_create.argtypes = [ctypes.POINTER(_Op), _i32, _i32, ctypes.POINTER(_vp)]
+        L.qasr_encoder_workspace_bytes.restype = ctypes.c_size_t
+        L.qasr_encoder_workspace_bytes.argtypes = [_vp]
+        L.qasr_encoder_forward.restype = _i32
+        L.qasr_encoder_forward.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.qasr_encoder_forward_timed.restype = _i32
+        L.qasr_encoder_forward_timed.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float)]
+        L.qasr_encoder_num_ops.restype = _i32
+        L.qasr_encoder_num_ops.argtypes = [_vp]
+        L.qasr_encoder_op_kernel.restype = ctypes.c_char_p
+        L.qasr_encoder_op_kernel.argtypes = [_vp, _i32]
+        L.qasr_encoder_destroy.restype = None
+        L.qasr_encoder_destroy.argtypes = [_vp]
+        L.qasr_conv1d_kernel_name.restype = ctypes.c_char_p
+        L.qasr_conv1d_kernel_name.argtypes = [dp]
+        L.qasr_last_hip_error.restype = ctypes.c_char_p
+        L.qasr_last_hip_error.argtypes = []
+        L.qasr_status_string.restype = ctypes.c_char_p
+        L.qasr_status_string.argtypes = [_i32]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().qasr_status_string(status).decode()
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise QasrError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_desc(B, Cin, Cout, Tin, k=1, stride=1, dilation=1, pad_left=0, pad_right=0, groups=1,
+              x_batch_stride=0, y_batch_stride=0, flags=0) -> ConvDesc:
+    return ConvDesc(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right, groups,
+                    x_batch_stride, y_batch_stride, flags)
+
+
+def conv1d_out_len(d: ConvDesc) -> int:
+    return int(lib().qasr_conv1d_out_len(ctypes.byref(d)))
+
+
+def conv1d_kernel_name(d: ConvDesc) -> Optional[str]:
+    r = lib().qasr_conv1d_kernel_name(ctypes.byref(d))
+    return r.decode() if r else None
+
+
+def conv1d_int8(d: ConvDesc, x, w, bias, m, s, residual, y):
+    """qasr_conv1d_int8 on torch CUDA tensors; y is written in place (asynchronously)."""
+    _check(lib().qasr_conv1d_int8(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(m), _ptr(s),
+                                  _ptr(residual), _ptr(y), _stream()), "qasr_conv1d_int8")
+    return y
+
+
+def packed_weight_bytes(d: ConvDesc) -> int:
+    return int(lib().qasr_packed_weight_bytes(ctypes.byref(d)))
+
+
+def pack_weights(d: ConvDesc, w, w_packed):
+    _check(lib().qasr_pack_weights(ctypes.byref(d), _ptr(w), _ptr(w_packed), _stream()), "qasr_pack_weights")
+    return w_packed
+
+
+def requant(acc, bias, m, s, residual, flags, y):
+    B, C, T = acc.shape
+    _check(lib().qasr_requant(_ptr(acc), B, C, T, _ptr(bias), _ptr(m), _ptr(s), _ptr(residual), flags,
+                              _ptr(y), _stream()), "qasr_requant")
+    return y
+
+
+class Encoder:
+    """qasr_encoder_* handle.  `ops` is a sequence of (ConvDesc, w, bias, m, s, in_slot, res_slot,
+    out_slot) with torch CUDA tensors, which the handle keeps alive."""
+
+    def __init__(self, ops: Sequence[tuple], n_slots: int):
+        self._keep = [o[1:5] for o in ops]
+        arr = (_Op * len(ops))()
+        for i, (d, w, bias, m, s, i_s, r_s, o_s) in enumerate(ops):
+            arr[i] = _Op(d, w.data_ptr(), bias.data_ptr() if bias is not None else None, m.data_ptr(),
+                         s.data_ptr(), i_s, r_s, o_s)
+        h = _vp()
+        _check(lib().qasr_encoder_create(arr, len(ops), n_slots, ctypes.byref(h)), "qasr_encoder_create")
+        self._h = h
+        self.n_ops = int(lib().qasr_encoder_num_ops(h))
+        self.workspace_bytes = int(lib().qasr_encoder_workspace_bytes(h))
+
+    def op_kernel(self, i: int) -> str:
+        return lib().qasr_encoder_op_kernel(self._h, i).decode()
+
+    def forward(self, x, y, workspace):
+        _check(lib().qasr_encoder_forward(self._h, _ptr(x), _ptr(y), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream()),
+               "qasr_encoder_forward")
+        return y
+
+    def forward_timed(self, x, y, workspace):
+        ms = (ctypes.c_float * self.n_ops)()
+        _check(lib().qasr_encoder_forward_timed(self._h, _ptr(x), _ptr(y), _ptr(workspace),
+                                                workspace.numel() * workspace.element_size(), _stream(), ms),
+               "qasr_encoder_forward_timed")
+        return list(ms)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().qasr_encoder_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,333 @@
+// C ABI of the library: argument validation (before any HIP call), kernel dispatch, and the
+// encoder executor (a flat op list over activation slots).  See include/qasr.h.
+#include "../../include/qasr.h"
+#include "kernels.hpp"
+
+#include <new>
+#include <vector>
+
+using qasr::ConvParams;
+
+namespace {
+
+thread_local hipError_t g_last_hip = hipSuccess;   // detail behind the last QASR_ERR_HIP
+
+qasr_status hip_status(hipError_t e) {
+  if (e == hipSuccess) return QASR_OK;
+  g_last_hip = e;
+  return QASR_ERR_HIP;
+}
+
+constexpr uint32_t kKnownFlags = QASR_FLAG_RELU | QASR_FLAG_W_PACKED;
+
+int64_t out_len64(const qasr_conv1d_desc* d) {
+  const int64_t span = (int64_t)d->Tin + d->pad_left + d->pad_right - (int64_t)d->dilation * (d->k - 1) - 1;
+  return span < 0 ? 0 : span / d->stride + 1;
+}
+
+qasr_status check_desc(const qasr_conv1d_desc* d) {
+  if (!d) return QASR_ERR_NULL;
+  if (d->B < 1 || d->Cin < 1 || d->Cout < 1 || d->Tin < 1 || d->k < 1 || d->stride < 1 ||
+      d->dilation < 1 || d->pad_left < 0 || d->pad_right < 0)
+    return QASR_ERR_SHAPE;
+  if (d->flags & ~kKnownFlags) return QASR_ERR_PARAM;
+  if (d->groups != 1 && !(d->groups == d->Cin && d->Cin == d->Cout)) return QASR_ERR_UNSUPPORTED;
+  const int64_t Tout = out_len64(d);
+  if (Tout < 1 || Tout > 0x7fffffffLL) return QASR_ERR_SHAPE;
+  if (d->x_batch_stride < 0 || d->y_batch_stride < 0) return QASR_ERR_SHAPE;
+  if (d->x_batch_stride && d->x_batch_stride < (int64_t)d->Cin * d->Tin) return QASR_ERR_SHAPE;
+  if (d->y_batch_stride && d->y_batch_stride < (int64_t)d->Cout * Tout) return QASR_ERR_SHAPE;
+  return QASR_OK;
+}
+
+bool overlaps(const void* a, int64_t na, const void* b, int64_t nb) {
+  const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a0 < b0 + (uint64_t)nb && b0 < a0 + (uint64_t)na;
+}
+
+ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t* w, const int32_t* bias,
+                       const int32_t* m, const int32_t* s, const int8_t* res, int8_t* y) {
+  ConvParams p{};
+  p.x = x; p.w = w; p.bias = bias; p.m = m; p.s = s; p.res = res; p.y = y;
+  p.B = d->B; p.Cin = d->Cin; p.Cout = d->Cout; p.Tin = d->Tin; p.Tout = (int32_t)out_len64(d);
+  p.k = d->k; p.stride = d->stride; p.dil = d->dilation; p.pl = d->pad_left;
+  p.depthwise = d->groups != 1;
+  p.relu = (d->flags & QASR_FLAG_RELU) ? 1 : 0;
+  p.w_packed = (!p.depthwise && d->k > 1 && (d->flags & QASR_FLAG_W_PACKED)) ? 1 : 0;
+  p.xbs = d->x_batch_stride ? d->x_batch_stride : (int64_t)d->Cin * d->Tin;
+  p.ybs = d->y_batch_stride ? d->y_batch_stride : (int64_t)d->Cout * p.Tout;
+  return p;
+}
+
+enum class Kernel { Generic, DwMfma, GemmMfma };
+
+Kernel pick_kernel(const ConvParams& p) {
+  if (p.depthwise) return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
+  if ((p.k == 1 || p.w_packed) && qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
+  return Kernel::Generic;
+}
+
+const char* kernel_name(Kernel k) {
+  switch (k) {
+    case Kernel::DwMfma: return "dw_mfma";
+    case Kernel::GemmMfma: return "gemm_mfma";
+    default: return "conv_generic";
+  }
+}
+
+qasr_status launch(const ConvParams& p, hipStream_t st) {
+  hipError_t e;
+  switch (pick_kernel(p)) {
+    case Kernel::DwMfma: e = qasr::launch_dw_mfma(p, st); break;
+    case Kernel::GemmMfma: e = qasr::launch_gemm_mfma(p, st); break;
+    default: e = qasr::launch_conv_generic(p, st); break;
+  }
+  return hip_status(e);
+}
+
+size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+}  // namespace
+
+struct qasr_encoder {
+  struct Op {
+    qasr_conv1d_desc d;
+    ConvParams p;          // pointers to weights/constants filled in; x / res / y set per forward
+    int32_t in_slot, res_slot, out_slot;
+    Kernel kernel;
+  };
+  std::vector<Op> ops;
+  std::vector<size_t> slot_off;   // byte offset of slot i in the workspace (slot 0 unused)
+  size_t ws_bytes = 0;
+  int8_t* packed = nullptr;       // device: packed weights of all dense k>1 layers
+};
+
+extern "C" {
+
+int32_t qasr_conv1d_out_len(const qasr_conv1d_desc* d) {
+  const qasr_status st = check_desc(d);
+  if (st != QASR_OK) return (int32_t)st;
+  return (int32_t)out_len64(d);
+}
+
+const char* qasr_conv1d_kernel_name(const qasr_conv1d_desc* d) {
+  if (check_desc(d) != QASR_OK) return nullptr;
+  const ConvParams p = make_params(d, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+  return kernel_name(pick_kernel(p));
+}
+
+qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const int8_t* w,
+                             const int32_t* bias, const int32_t* m, const int32_t* s,
+                             const int8_t* residual, int8_t* y, void* stream) {
+  const qasr_status st = check_desc(d);
+  if (st != QASR_OK) return st;
+  if (!x || !w || !m || !s || !y) return QASR_ERR_NULL;
+  const ConvParams p = make_params(d, x, w, bias, m, s, residual, y);
+  const int64_t ny = (int64_t)(p.B - 1) * p.ybs + (int64_t)p.Cout * p.Tout;
+  const int64_t nx = (int64_t)(p.B - 1) * p.xbs + (int64_t)p.Cin * p.Tin;
+  if (overlaps(y, ny, x, nx) || (residual && overlaps(y, ny, residual, ny))) return QASR_ERR_ALIAS;
+  return launch(p, (hipStream_t)stream);
+}
+
+size_t qasr_packed_weight_bytes(const qasr_conv1d_desc* d) {
+  if (check_desc(d) != QASR_OK) return 0;
+  const int64_t cin_g = d->groups != 1 ? 1 : d->Cin;
+  return (size_t)((int64_t)d->Cout * cin_g * d->k);
+}
+
+qasr_status qasr_pack_weights(const qasr_conv1d_desc* d, const int8_t* w, int8_t* w_packed, void* stream) {
+  const qasr_status st = check_desc(d);
+  if (st != QASR_OK) return st;
+  if (!w || !w_packed) return QASR_ERR_NULL;
+  const size_t n = qasr_packed_weight_bytes(d);
+  if (overlaps(w, (int64_t)n, w_packed, (int64_t)n)) return QASR_ERR_ALIAS;
+  hipError_t e;
+  if (d->groups != 1 || d->k == 1)   // packed form == plain form
+    e = hipMemcpyAsync(w_packed, w, n, hipMemcpyDeviceToDevice, (hipStream_t)stream);
+  else
+    e = qasr::launch_pack_weights(w, w_packed, d->Cout, d->Cin, d->k, (hipStream_t)stream);
+  return hip_status(e);
+}
+
+qasr_status qasr_requant(const int32_t* acc, int32_t B, int32_t C, int32_t T, const int32_t* bias,
+                         const int32_t* m, const int32_t* s, const int8_t* residual, uint32_t flags,
+                         int8_t* y, void* stream) {
+  if (!acc || !m || !s || !y) return QASR_ERR_NULL;
+  if (B < 1 || C < 1 || T < 1) return QASR_ERR_SHAPE;
+  if (flags & ~(uint32_t)QASR_FLAG_RELU) return QASR_ERR_PARAM;
+  const int64_t n = (int64_t)B * C * T;
+  if (overlaps(y, n, acc, 4 * n) || (residual && overlaps(y, n, residual, n))) return QASR_ERR_ALIAS;
+  const hipError_t e = qasr::launch_requant(acc, B, C, T, bias, m, s, residual,
+                                            (flags & QASR_FLAG_RELU) ? 1 : 0, y, (hipStream_t)stream);
+  return hip_status(e);
+}
+
+qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slots, qasr_encoder** out) {
+  if (!ops || !out) return QASR_ERR_NULL;
+  if (n_ops < 1 || n_slots < 2) return QASR_ERR_SHAPE;
+  *out = nullptr;
+
+  // ---- validation: host only, no HIP call yet
+  struct SlotState { bool live = false; int32_t C = 0, T = 0; };
+  std::vector<SlotState> slot(n_slots);
+  std::vector<size_t> slot_bytes(n_slots, 0);
+  size_t packed_bytes = 0;
+  for (int32_t i = 0; i < n_ops; ++i) {
+    const qasr_op& o = ops[i];
+    const qasr_status st = check_desc(&o.d);
+    if (st != QASR_OK) return st;
+    if (!o.w || !o.m || !o.s) return QASR_ERR_NULL;
+    if (o.d.flags & QASR_FLAG_W_PACKED) return QASR_ERR_PARAM;
+    if (o.d.y_batch_stride != 0) return QASR_ERR_PARAM;
+    if (o.d.B != ops[0].d.B) return QASR_ERR_SHAPE;
+    if (o.in_slot < 0 || o.in_slot >= n_slots || o.out_slot < 1 || o.out_slot >= n_slots ||
+        o.res_slot < -1 || o.res_slot >= n_slots)
+      return QASR_ERR_PARAM;
+    if (o.out_slot == o.in_slot || o.out_slot == o.res_slot) return QASR_ERR_PARAM;
+    if (i == 0) {
+      if (ops[0].in_slot != 0) return QASR_ERR_PARAM;
+      slot[0].live = true;
+      slot[0].T = o.d.Tin;
+      slot[0].C = o.d.x_batch_stride ? (int32_t)(o.d.x_batch_stride / o.d.Tin) : o.d.Cin;
+    }
+    const SlotState& in = slot[o.in_slot];
+    if (!in.live || in.T != o.d.Tin) return QASR_ERR_PARAM;
+    if (o.d.x_batch_stride == 0 ? in.C != o.d.Cin
+                                : (o.d.x_batch_stride != (int64_t)in.C * in.T || o.d.Cin > in.C))
+      return QASR_ERR_PARAM;
+    const int32_t Tout = (int32_t)out_len64(&o.d);
+    if (o.res_slot >= 0) {
+      const SlotState& r = slot[o.res_slot];
+      if (!r.live || r.C != o.d.Cout || r.T != Tout) return QASR_ERR_PARAM;
+    }
+    slot[o.out_slot].live = true;
+    slot[o.out_slot].C = o.d.Cout;
+    slot[o.out_slot].T = Tout;
+    const size_t bytes = (size_t)o.d.B * o.d.Cout * Tout;
+    if (bytes > slot_bytes[o.out_slot]) slot_bytes[o.out_slot] = bytes;
+    if (o.d.groups == 1 && o.d.k > 1) packed_bytes += round256((size_t)o.d.Cout * o.d.Cin * o.d.k);
+  }
+
+  qasr_encoder* e = new (std::nothrow) qasr_encoder();
+  if (!e) return QASR_ERR_HIP;
+  e->slot_off.assign(n_slots, 0);
+  size_t off = 0;
+  for (int32_t sidx = 1; sidx < n_slots; ++sidx) {
+    e->slot_off[sidx] = off;
+    off += round256(slot_bytes[sidx]);
+  }
+  e->ws_bytes = off;
+
+  // ---- one-time device work: pack the dense k>1 weights
+  if (packed_bytes) {
+    const hipError_t me = hipMalloc((void**)&e->packed, packed_bytes);
+    if (me != hipSuccess) { delete e; return hip_status(me); }
+  }
+  size_t poff = 0;
+  e->ops.resize(n_ops);
+  for (int32_t i = 0; i < n_ops; ++i) {
+    const qasr_op& o = ops[i];
+    qasr_encoder::Op& op = e->ops[i];
+    op.d = o.d;
+    op.in_slot = o.in_slot; op.res_slot = o.res_slot; op.out_slot = o.out_slot;
+    const int8_t* w = o.w;
+    if (o.d.groups == 1 && o.d.k > 1) {
+      int8_t* wp = e->packed + poff;
+      poff += round256((size_t)o.d.Cout * o.d.Cin * o.d.k);
+      const hipError_t pe = qasr::launch_pack_weights(o.w, wp, o.d.Cout, o.d.Cin, o.d.k, nullptr);
+      if (pe != hipSuccess) {
+        qasr_encoder_destroy(e);
+        return hip_status(pe);
+      }
+      w = wp;
+      op.d.flags |= QASR_FLAG_W_PACKED;
+    }
+    op.p = make_params(&op.d, nullptr, w, o.bias, o.m, o.s, nullptr, nullptr);
+    op.kernel = pick_kernel(op.p);
+  }
+  if (packed_bytes) {
+    const hipError_t se = hipStreamSynchronize(nullptr);
+    if (se != hipSuccess) {
+      qasr_encoder_destroy(e);
+      return hip_status(se);
+    }
+  }
+  *out = e;
+  return QASR_OK;
+}
+
+size_t qasr_encoder_workspace_bytes(const qasr_encoder* e) { return e ? e->ws_bytes : 0; }
+
+int32_t qasr_encoder_num_ops(const qasr_encoder* e) { return e ? (int32_t)e->ops.size() : 0; }
+
+const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i) {
+  if (!e || i < 0 || i >= (int32_t)e->ops.size()) return nullptr;
+  return kernel_name(e->ops[i].kernel);
+}
+
+static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
+                                size_t workspace_bytes, hipStream_t st, hipEvent_t* ev) {
+  if (!e || !x || !y) return QASR_ERR_NULL;
+  if (e->ws_bytes && (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < e->ws_bytes))
+    return QASR_ERR_WORKSPACE;
+  int8_t* ws = (int8_t*)workspace;
+  const size_t n = e->ops.size();
+  for (size_t i = 0; i < n; ++i) {
+    const qasr_encoder::Op& op = e->ops[i];
+    ConvParams p = op.p;
+    p.x = op.in_slot == 0 ? x : ws + e->slot_off[op.in_slot];
+    p.res = op.res_slot < 0 ? nullptr : (op.res_slot == 0 ? x : ws + e->slot_off[op.res_slot]);
+    p.y = (i + 1 == n) ? y : ws + e->slot_off[op.out_slot];
+    if (ev) { const hipError_t re = hipEventRecord(ev[i], st); if (re != hipSuccess) return hip_status(re); }
+    const qasr_status s = launch(p, st);
+    if (s != QASR_OK) return s;
+  }
+  if (ev) { const hipError_t re = hipEventRecord(ev[n], st); if (re != hipSuccess) return hip_status(re); }
+  return QASR_OK;
+}
+
+qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  return forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
+                                       size_t workspace_bytes, void* stream, float* op_ms) {
+  if (!e || !op_ms) return QASR_ERR_NULL;
+  const size_t n = e->ops.size();
+  std::vector<hipEvent_t> ev(n + 1, nullptr);
+  qasr_status st = QASR_OK;
+  for (size_t i = 0; i <= n && st == QASR_OK; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) st = QASR_ERR_HIP;
+  if (st == QASR_OK) st = forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, ev.data());
+  if (st == QASR_OK && hipEventSynchronize(ev[n]) != hipSuccess) st = QASR_ERR_HIP;
+  for (size_t i = 0; i < n && st == QASR_OK; ++i)
+    if (hipEventElapsedTime(&op_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = QASR_ERR_HIP;
+  for (hipEvent_t v : ev)
+    if (v) (void)hipEventDestroy(v);
+  return st;
+}
+
+void qasr_encoder_destroy(qasr_encoder* e) {
+  if (!e) return;
+  if (e->packed) (void)hipFree(e->packed);
+  delete e;
+}
+
+const char* qasr_last_hip_error(void) { return hipGetErrorName(g_last_hip); }
+
+const char* qasr_status_string(qasr_status st) {
+  switch (st) {
+    case QASR_OK: return "ok";
+    case QASR_ERR_NULL: return "required pointer is NULL";
+    case QASR_ERR_SHAPE: return "invalid shape";
+    case QASR_ERR_PARAM: return "invalid parameter";
+    case QASR_ERR_UNSUPPORTED: return "unsupported grouping";
+    case QASR_ERR_ALIAS: return "output overlaps an input";
+    case QASR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case QASR_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,60 @@
+// Shared device helpers and launch-parameter structs of the HIP path (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qasr {
+
+// Geometry + pointers of one layer, passed by value to every convolution kernel.
+struct ConvParams {
+  const int8_t* x;
+  const int8_t* w;
+  const int32_t* bias;   // may be null
+  const int32_t* m;
+  const int32_t* s;
+  const int8_t* res;     // may be null
+  int8_t* y;
+  int64_t xbs, ybs;      // batch strides in elements
+  int32_t B, Cin, Cout, Tin, Tout;
+  int32_t k, stride, dil, pl;
+  int32_t depthwise;     // 0: groups == 1, 1: groups == Cin == Cout
+  int32_t relu;
+  int32_t w_packed;      // dense k>1 weights are [k][Cout][Cin] instead of [Cout][Cin][k]
+};
+
+// Dyadic rescale v = floor((A*m + 2^(s-1)) / 2^s), 0 <= m < 2^31, 1 <= s <= 62, returned
+// clamped to [-2^20, 2^20] (the caller adds an int8 residual and clamps to int8 next, so any
+// value beyond +-256 is equivalent).
+//
+// For s >= 33 write A*m = H*2^32 + L with 0 <= L < 2^32 and H = mulhi(A, m).  Then
+// floor((A*m + 2^(s-1)) / 2^s) = floor((H + 2^(s-33) + L/2^32) / 2^(s-32)); the numerator's
+// integer part has a fractional remainder of at most 1 - 2^-(s-32) after division and
+// L/2^s < 2^-(s-32) cannot carry, so the result is (H + 2^(s-33)) >> (s-32): one high
+// multiply, one add, one arithmetic shift.  Smaller s takes the 64-bit form.
+__device__ __forceinline__ int32_t dyadic_rescale(int32_t A, int32_t m, int32_t s) {
+  if (s >= 33) {
+    const int32_t h = __mulhi(A, m);
+    return (h + (1 << (s - 33))) >> (s - 32);
+  }
+  long long v = ((long long)A * (long long)m + (1ll << (s - 1))) >> s;
+  v = v > (1 << 20) ? (1 << 20) : v;
+  v = v < -(1 << 20) ? -(1 << 20) : v;
+  return (int32_t)v;
+}
+
+// Launch through hipLaunchKernel so that the status returned is this launch's own (the
+// thread-wide "last error" may hold a stale, unrelated value left by other HIP users).
+// Arguments are converted to the kernel's own parameter types before their addresses are taken.
+template <typename T> struct same_type { using type = T; };
+template <typename... KArgs>
+inline hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem,
+                                hipStream_t st, typename same_type<KArgs>::type... args) {
+  void* argv[] = {(void*)&args...};
+  return hipLaunchKernel((const void*)kernel, grid, block, argv, shmem, st);
+}
+
+__device__ __forceinline__ int32_t clamp_i8(int32_t v, int32_t lo) {
+  return min(127, max(lo, v));
+}
+
+}  // namespace qasr

@@ -1,0 +1,28 @@
+// Host-callable launchers of the HIP kernels (one translation unit each).
+#pragma once
+#include "common.hpp"
+
+namespace qasr {
+
+// Generic direct convolution: any stride / dilation / padding / channel count, dense or
+// depthwise.  One thread per output element.  The fallback for geometries the MFMA kernels
+// do not take.
+hipError_t launch_conv_generic(const ConvParams& p, hipStream_t st);
+
+// Standalone epilogue on int32 accumulators.
+hipError_t launch_requant(const int32_t* acc, int B, int C, int T, const int32_t* bias,
+                          const int32_t* m, const int32_t* s, const int8_t* res, int relu,
+                          int8_t* y, hipStream_t st);
+
+// [Cout][Cin][k] -> [k][Cout][Cin]
+hipError_t launch_pack_weights(const int8_t* w, int8_t* wp, int Cout, int Cin, int k, hipStream_t st);
+
+// Depthwise convolution as a banded-Toeplitz product on the int8 matrix cores (stride 1).
+bool dw_mfma_supported(const ConvParams& p);
+hipError_t launch_dw_mfma(const ConvParams& p, hipStream_t st);
+
+// Pointwise / dense convolution as an implicit GEMM on the int8 matrix cores.
+bool gemm_mfma_supported(const ConvParams& p);
+hipError_t launch_gemm_mfma(const ConvParams& p, hipStream_t st);
+
+}  // namespace qasr

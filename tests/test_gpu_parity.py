@@ -1,0 +1,271 @@
+"""Bit-exact parity of the HIP path (through the C ABI) against the CPU oracle.
+
+Every case prints its name before touching the GPU, so that a fault can be traced to a
+case from the tail of the log.  Integer results: the bar is equality of every byte.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2103_16827_amd as Q
+import qasr_workloads as W
+from qasr_workloads.rng import randint_array
+from qasr_workloads.nets import OpSpec, FLAG_RELU
+from gpu_util import dev, desc_of, gpu_layer, GpuNet
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def draw(seed, shape, lo, hi, dtype):
+    return randint_array(seed, shape, lo, hi, dtype)
+
+
+# ----------------------------------------------------------------------------- qasr_requant
+@pytest.mark.parametrize("B,C,T", [(1, 1, 1), (2, 3, 17), (1, 5, 16), (2, 7, 200), (3, 64, 800), (1, 256, 1000), (2, 2, 4099)])
+@pytest.mark.parametrize("mode", ["config", "generic"])
+def test_requant(B, C, T, mode):
+    say(f"requant B={B} C={C} T={T} mode={mode}")
+    sd = 100 * B + 10 * C + T
+    acc = draw(sd, (B, C, T), -(1 << 28), 1 << 28, np.int32)
+    acc.reshape(-1)[:5] = [-(1 << 31), (1 << 31) - 1, 0, -1, 1][: min(5, acc.size)]
+    if mode == "config":
+        m = draw(sd + 1, (C,), 1 << 30, (1 << 31) - 1, np.int32)
+        s = draw(sd + 2, (C,), 36, 58, np.int32)
+    else:
+        m = draw(sd + 1, (C,), 0, (1 << 31) - 1, np.int32)
+        s = draw(sd + 2, (C,), 1, 62, np.int32)
+        m[0], s[0] = 1 << 30, 30            # the identity pair
+        if C > 2:
+            s[1], s[2] = 32, 33             # both sides of the fast-path boundary
+    bias = draw(sd + 3, (C,), -(1 << 16), 1 << 16, np.int32)
+    res = draw(sd + 4, (B, C, T), -128, 127, np.int8)
+    for use_bias, use_res, relu in ((True, True, False), (False, False, True), (True, False, False), (False, True, True)):
+        b_ = bias if use_bias else None
+        r_ = res if use_res else None
+        if use_bias:
+            a = np.clip(acc.astype(np.int64), -(1 << 31) + (1 << 16), (1 << 31) - 1 - (1 << 16)).astype(np.int32)
+        else:
+            a = acc
+        ref = oracle.requant(a, b_, m, s, r_, relu)
+        y = torch.full((B, C, T), 55, dtype=torch.int8, device="cuda")
+        Q.requant(dev(a), dev(b_), dev(m), dev(s), dev(r_), Q.FLAG_RELU if relu else 0, y)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), ref), (use_bias, use_res, relu)
+
+
+# ----------------------------------------------------------------------------- single layers
+def layer_case(name, B, Cin, Cout, T, k=1, stride=1, dil=1, pad=None, dw=False, relu=True, bias=True,
+               res=False, seed=1, wmin=-127, s_lo=36, s_hi=44, packed=False, prefix_of=None):
+    if pad is None:
+        tot = dil * (k - 1)
+        pad = (tot // 2, tot - tot // 2)
+    xbs = prefix_of * T if prefix_of else 0
+    op = OpSpec(name, Cin, Cout, T, k, stride, dil, pad[0], pad[1], Cin if dw else 1, xbs,
+                FLAG_RELU if relu else 0, bias)
+    Cx = prefix_of or Cin
+    sd = seed * 7919 + Cin * 31 + Cout * 17 + T + k
+    x = draw(sd, (B, Cx, T), -128, 127, np.int8)
+    p = {"w": draw(sd + 1, (Cout, 1 if dw else Cin, k), wmin, 127, np.int8),
+         "bias": draw(sd + 2, (Cout,), -(1 << 16), 1 << 16, np.int32) if bias else None,
+         "m": draw(sd + 3, (Cout,), 1 << 30, (1 << 31) - 1, np.int32),
+         "s": draw(sd + 4, (Cout,), s_lo, s_hi, np.int32)}
+    r = draw(sd + 5, (B, Cout, op.Tout), -128, 127, np.int8) if res else None
+    return op, p, x, r, packed
+
+
+def run_layer_case(case):
+    op, p, x, r, packed = case
+    B = x.shape[0]
+    kern = Q.conv1d_kernel_name(desc_of(op, B, Q.FLAG_W_PACKED if packed else 0))
+    say(f"layer {op.name} B={B} Cin={op.Cin} Cout={op.Cout} T={op.Tin} k={op.k} s={op.stride} d={op.dilation} "
+        f"pad=({op.pad_left},{op.pad_right}) dw={op.depthwise} packed={packed} -> {kern}")
+    ref = oracle.run_op(op, p, x, r)
+    got = gpu_layer(op, B, p, x, r, packed=packed)
+    bad = np.argwhere(got != ref)
+    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[tuple(bad[0])]} want {ref[tuple(bad[0])]}"
+    return kern
+
+
+SMALL = [
+    dict(name="tiny_pw", B=1, Cin=1, Cout=1, T=1),
+    dict(name="odd_pw", B=2, Cin=5, Cout=7, T=9, res=True),
+    dict(name="odd_dense", B=2, Cin=3, Cout=5, T=17, k=3, stride=2, dil=2, pad=(2, 1), res=True, relu=False),
+    dict(name="odd_dw", B=2, Cin=5, Cout=5, T=23, k=5, dw=True, pad=(1, 3), bias=False, relu=False),
+    dict(name="dw_stride2", B=1, Cin=8, Cout=8, T=40, k=3, stride=2, dw=True),
+    dict(name="dw_longer_than_T", B=2, Cin=4, Cout=4, T=7, k=33, dw=True, bias=False),
+    dict(name="dense_minus128", B=1, Cin=16, Cout=8, T=33, k=5, wmin=-128),
+    dict(name="k_even", B=1, Cin=8, Cout=8, T=30, k=4, dw=True, pad=(1, 2)),
+    dict(name="generic_s", B=1, Cin=6, Cout=6, T=12, k=3, s_lo=1, s_hi=35),
+    dict(name="dense_packed_odd", B=1, Cin=6, Cout=10, T=21, k=3, packed=True, res=True),
+]
+
+
+@pytest.mark.parametrize("kw", SMALL, ids=[c["name"] for c in SMALL])
+def test_small_and_odd_layers(kw):
+    run_layer_case(layer_case(**kw))
+
+
+# Shapes of the benchmark networks (one or two batch items keep the oracle in seconds) plus
+# ragged variants that span several tiles and a tail.
+REAL = [
+    dict(name="cfg0_dw", B=1, Cin=256, Cout=256, T=200, k=33, dw=True, bias=False, relu=False),
+    dict(name="cfg0_pw", B=1, Cin=256, Cout=256, T=200),
+    dict(name="dw_k33", B=2, Cin=256, Cout=256, T=800, k=33, dw=True, bias=False, relu=False),
+    dict(name="dw_k39", B=2, Cin=256, Cout=256, T=800, k=39, dw=True, bias=False, relu=False),
+    dict(name="dw_k51", B=1, Cin=512, Cout=512, T=800, k=51, dw=True, bias=False, relu=False),
+    dict(name="dw_k63", B=1, Cin=512, Cout=512, T=800, k=63, dw=True, bias=False, relu=False),
+    dict(name="dw_k75", B=1, Cin=512, Cout=512, T=800, k=75, dw=True, bias=False, relu=False),
+    dict(name="dw_k87_d2", B=1, Cin=512, Cout=512, T=800, k=87, dil=2, dw=True, bias=False, relu=False),
+    dict(name="dw_k32_prefix", B=2, Cin=512, Cout=512, T=400, k=32, dw=True, bias=False, relu=False, prefix_of=1024),
+    dict(name="dw_ragged_T", B=3, Cin=70, Cout=70, T=1037, k=39, dw=True, bias=True, relu=True, res=True),
+    dict(name="dw_T_not4", B=2, Cin=33, Cout=33, T=203, k=33, dw=True, bias=True, res=True),
+    dict(name="dw_long_T", B=1, Cin=16, Cout=16, T=5000, k=75, dw=True, bias=False),
+    dict(name="dw_minus128", B=1, Cin=64, Cout=64, T=320, k=33, dw=True, wmin=-128, bias=False),
+    dict(name="dw_generic_s", B=1, Cin=64, Cout=64, T=320, k=33, dw=True, s_lo=20, s_hi=40),
+    dict(name="pw_256_256", B=2, Cin=256, Cout=256, T=800),
+    dict(name="pw_256_512_res", B=1, Cin=256, Cout=512, T=800, relu=False),
+    dict(name="pw_512_512_res", B=2, Cin=512, Cout=512, T=800, res=True),
+    dict(name="pw_512_1024", B=1, Cin=512, Cout=1024, T=800),
+    dict(name="pw_1024_29", B=2, Cin=1024, Cout=29, T=800, relu=False),
+    dict(name="pw_2048_512", B=1, Cin=2048, Cout=512, T=400, relu=False),
+    dict(name="pw_ragged", B=3, Cin=192, Cout=200, T=333, res=True),
+    dict(name="pw_T_not4", B=2, Cin=128, Cout=64, T=203, res=True),
+    dict(name="pw_minus128", B=1, Cin=128, Cout=64, T=160, wmin=-128),
+    dict(name="pw_generic_s", B=1, Cin=128, Cout=64, T=160, s_lo=20, s_hi=40),
+    dict(name="c1_dense_s2", B=2, Cin=64, Cout=256, T=1600, k=33, stride=2, pad=(16, 16), packed=True),
+    dict(name="c1_dense_s2_raw", B=1, Cin=64, Cout=256, T=400, k=33, stride=2, pad=(16, 16)),
+    dict(name="jasper_k11", B=1, Cin=256, Cout=256, T=800, k=11, packed=True, res=True),
+    dict(name="jasper_k13_384", B=1, Cin=384, Cout=384, T=400, k=13, packed=True),
+    dict(name="jasper_k25_768", B=1, Cin=768, Cout=768, T=200, k=25, packed=True),
+    dict(name="jasper_pro", B=1, Cin=64, Cout=256, T=1600, k=11, stride=2, pad=(5, 5), packed=True),
+    dict(name="jasper_epi_d2", B=1, Cin=768, Cout=896, T=200, k=29, dil=2, packed=True),
+    dict(name="dense_ragged", B=2, Cin=128, Cout=72, T=211, k=7, packed=True, res=True),
+]
+
+
+@pytest.mark.parametrize("kw", REAL, ids=[c["name"] for c in REAL])
+def test_real_shape_layers(kw):
+    run_layer_case(layer_case(**kw))
+
+
+def test_benchmark_shapes_use_the_matrix_core_kernels():
+    """The fast kernels, not the generic fallback, serve every op of the benchmark networks."""
+    for cfg in range(5):
+        net = W.build_config(cfg)
+        for o in net.ops:
+            flags = Q.FLAG_W_PACKED if (not o.depthwise and o.k > 1) else 0
+            name = Q.conv1d_kernel_name(desc_of(o, net.B, flags))
+            assert name == ("dw_mfma" if o.depthwise else "gemm_mfma"), (cfg, o.name, name)
+
+
+# ----------------------------------------------------------------------------- encoders
+def check_encoder(net, seed, items=None):
+    """GPU forward of the whole batch vs the oracle on the chosen batch items (each item of the
+    batch is an independent utterance, so its output equals the oracle run on that item alone)."""
+    params = W.draw_net_params(net, seed)
+    x = W.draw_input(net, seed)
+    g = GpuNet(net, params)
+    y = g.forward(dev(x)).cpu().numpy()
+    torch.cuda.synchronize()
+    items = list(range(net.B)) if items is None else items
+    for b in items:
+        say(f"  oracle on {net.name} seed={seed} item {b}")
+        sub = W.NetSpec(net.name, net.config_id, 1, net.Cin, net.Tin, net.ops, net.n_slots)
+        ref, outs = oracle.encoder_forward(sub, params, np.ascontiguousarray(x[b:b + 1]), keep=True)
+        if not np.array_equal(y[b:b + 1], ref):
+            # localise: replay op by op on the GPU from the oracle's intermediates
+            slots = {0: x[b:b + 1]}
+            for i, (op, p) in enumerate(zip(net.ops, params)):
+                r = slots[op.res_slot] if op.res_slot >= 0 else None
+                got = gpu_layer(op, 1, p, slots[op.in_slot], r, packed=(not op.depthwise and op.k > 1))
+                assert np.array_equal(got, outs[i]), f"first failing op {i} {op.name} ({g.kernels()[i]})"
+                slots[op.out_slot] = outs[i]
+            raise AssertionError("encoder output differs although every op matches in isolation")
+        flat = ref.reshape(-1)
+        assert len(set(flat.tolist())) > 16, "degenerate reference output"
+    g.enc.close()
+    return y
+
+
+@pytest.mark.parametrize("seed", range(1, 21))
+def test_config0_separable_module(seed):
+    say(f"config0 seed={seed}")
+    check_encoder(W.build_config(0), seed)
+
+
+@pytest.mark.parametrize("cfg", range(5))
+def test_tiny_encoders(cfg):
+    say(f"tiny encoder {cfg}")
+    net = W.tiny_config(cfg)
+    params = W.draw_net_params(net, 3, s_lo=37, s_hi=38, bias_mag=300)
+    x = W.draw_input(net, 3)
+    g = GpuNet(net, params)
+    y = g.forward(dev(x)).cpu().numpy()
+    assert np.array_equal(y, oracle.encoder_forward(net, params, x))
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_config1_quartznet_5x5(seed):
+    say(f"config1 seed={seed}")
+    check_encoder(W.build_config(1), seed)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_config2_quartznet_15x5_batch32(seed):
+    """Full size, the launch configuration the benchmark times; oracle on sampled items."""
+    say(f"config2 seed={seed}")
+    check_encoder(W.build_config(2), seed, items=[0, 31] if seed == 1 else [seed * 7])
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_config3_jasper_10x5_batch16(seed):
+    say(f"config3 seed={seed}")
+    if seed == 1:
+        check_encoder(W.build_config(3), seed, items=[15])
+    else:
+        # other seeds at a quarter of the frames (same ops, B=2): keeps the oracle to seconds
+        check_encoder(W.jasper(2, 400, config_id=3), seed)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_config4_conformer_shaped_batch16(seed):
+    say(f"config4 seed={seed}")
+    check_encoder(W.build_config(4), seed, items=[seed])
+
+
+def test_forward_is_deterministic_and_leaves_guard_bytes():
+    """Integer results: any run-to-run difference would be a race.  Also checks that nothing
+    is written past the output tensor."""
+    net = W.build_config(1)
+    params = W.draw_net_params(net, 5)
+    x = dev(W.draw_input(net, 5))
+    g = GpuNet(net, params)
+    n = g.y.numel()
+    buf = torch.full((n + 4096,), 91, dtype=torch.int8, device="cuda")
+    outs = []
+    for _ in range(3):
+        g.ws.fill_(-7)
+        g.enc.forward(x, buf, g.ws)
+        torch.cuda.synchronize()
+        outs.append(buf[:n].clone())
+        assert bool((buf[n:] == 91).all())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_workspace_errors():
+    net = W.tiny_config(1)
+    params = W.draw_net_params(net, 1)
+    g = GpuNet(net, params)
+    x = dev(W.draw_input(net, 1))
+    small = torch.empty(16, dtype=torch.int8, device="cuda")
+    with pytest.raises(Q.QasrError) as e:
+        g.enc.forward(x, g.y, small)
+    assert e.value.status == -6
