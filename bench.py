@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the INT8 encoder hot path on one MI355X.
+
+A "step" is one qasr_encoder_forward of the QuartzNet-15x5-shaped encoder at batch 32,
+T=1600 input frames (benchmark config 2), on seeded synthetic int8 inputs and random int8
+weights already resident in HBM.  Prints ONE JSON line:
+
+  value       input frames per second (B*T_in*steps / wall time of the timed steps)
+  roofline    for the kernel family with the largest share of device time, measured live with
+              HIP events around every op (a separate, untimed-for-`value` pass)
+  stages      spec view: depthwise stages against HBM peak, pointwise stages against the
+              int8 MFMA peak (algorithmic bytes / MACs over summed per-op device time)
+  cpu_baseline the CPU oracle timed on a bounded sample (one batch item) on the host cores
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+INT8_PEAK_TOPS = 5000.0        # MI355X dense int8 MFMA, published (5.0 POP/s)
+
+
+def op_algorithmic(op, B):
+    """Algorithmic HBM bytes and MACs of one op: input + output (+ residual) int8 tensors,
+    weights and per-channel constants once."""
+    n_in = B * op.Cin * op.Tin
+    n_out = B * op.Cout * op.Tout
+    w = op.weight_count()
+    consts = op.Cout * (8 + (4 if op.has_bias else 0))
+    byts = n_in + n_out + (n_out if op.res_slot >= 0 else 0) + w + consts
+    return byts, op.macs(B)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (default 2)")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-passes", type=int, default=5, help="per-op timed passes for the roofline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (batch sharding across GPUs needs no kernel work "
+              "and is not part of it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2103_16827_amd as Q
+    from paper_2103_16827_amd.binding import make_desc
+    import qasr_workloads as W
+
+    torch.cuda.set_device(0)
+    net = W.build_config(args.config)
+    params = W.draw_net_params(net, args.seed)
+    x_host = W.draw_input(net, args.seed)
+
+    dev = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    dparams = [{k: dev(v) for k, v in p.items()} for p in params]
+    ops = [(make_desc(net.B, o.Cin, o.Cout, o.Tin, o.k, o.stride, o.dilation, o.pad_left, o.pad_right,
+                      o.groups, o.x_batch_stride, 0, o.flags), d["w"], d["bias"], d["m"], d["s"],
+            o.in_slot, o.res_slot, o.out_slot) for o, d in zip(net.ops, dparams)]
+    enc = Q.Encoder(ops, net.n_slots)
+    ws = torch.empty(max(enc.workspace_bytes, 256), dtype=torch.int8, device="cuda")
+    y = torch.empty((net.B, net.Cout, net.Tout), dtype=torch.int8, device="cuda")
+    x = dev(x_host)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        enc.forward(x, y, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        enc.forward(x, y, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_wall0
+    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step_events = e0.elapsed_time(e1) / args.steps
+    frames = net.B * net.Tin
+    value = frames / (ms_per_step * 1e-3)
+
+    # ---- per-op device time (HIP events on the launch stream, inside the library)
+    kernels = [enc.op_kernel(i) for i in range(enc.n_ops)]
+    acc_ms = np.zeros(enc.n_ops)
+    for _ in range(max(1, args.profile_passes)):
+        acc_ms += np.array(enc.forward_timed(x, y, ws))
+    op_ms = acc_ms / max(1, args.profile_passes)
+
+    fam = {}
+    for i, (o, k) in enumerate(zip(net.ops, kernels)):
+        byts, macs = op_algorithmic(o, net.B)
+        f = fam.setdefault(k, {"ms": 0.0, "bytes": 0, "macs": 0, "launches": 0})
+        f["ms"] += op_ms[i]; f["bytes"] += byts; f["macs"] += macs; f["launches"] += 1
+    dom = max(fam, key=lambda k: fam[k]["ms"])
+    d = fam[dom]
+    avg_ms = d["ms"] / d["launches"]
+    if dom == "dw_mfma" or dom == "conv_generic":
+        achieved = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None}
+    else:
+        achieved = 2.0 * d["macs"] / d["launches"] / (avg_ms * 1e-3) / 1e12
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": achieved / INT8_PEAK_TOPS, "traffic": None}
+    roofline["avg_launch_us"] = avg_ms * 1e3
+    roofline["launches_per_step"] = d["launches"]
+    roofline["share_of_device_time"] = d["ms"] / float(op_ms.sum())
+
+    def stage(sel):
+        idx = [i for i, o in enumerate(net.ops) if sel(o)]
+        if not idx:
+            return None
+        ms = float(op_ms[idx].sum())
+        byts = sum(op_algorithmic(net.ops[i], net.B)[0] for i in idx)
+        macs = sum(op_algorithmic(net.ops[i], net.B)[1] for i in idx)
+        return {"ops": len(idx), "ms": ms, "GB/s": byts / (ms * 1e-3) / 1e9, "hbm_frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "TOP/s": 2 * macs / (ms * 1e-3) / 1e12, "mfma_frac": 2 * macs / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS}
+    stages = {"depthwise": stage(lambda o: o.depthwise),
+              "pointwise": stage(lambda o: not o.depthwise and o.k == 1),
+              "dense": stage(lambda o: not o.depthwise and o.k > 1),
+              "device_ms_sum": float(op_ms.sum()), "ms_per_step_events": ms_per_step_events}
+
+    # ---- the oracle on the host cores, on one batch item of the same workload
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sub = W.NetSpec(net.name, net.config_id, 1, net.Cin, net.Tin, net.ops, net.n_slots)
+        xs = np.ascontiguousarray(x_host[:1])
+        t0 = time.perf_counter()
+        ref = oracle.encoder_forward(sub, params, xs)
+        dt = time.perf_counter() - t0
+        ok = bool(np.array_equal(ref, y[:1].cpu().numpy()))
+        cpu = {"value": net.Tin / dt, "unit": "frames/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"batch item 0 of the same workload ({net.Tin} frames, {W.net_macs(sub) / 1e9:.1f} GMAC) in {dt:.2f} s",
+               "gpu_output_matches": ok}
+
+    total_macs = W.net_macs(net)
+    out = {
+        "metric": "INT8 encoder frames/sec", "value": value, "unit": "frames/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {net.name} B={net.B} T_in={net.Tin} ({len(net.ops)} ops)",
+                   "seed": args.seed, "parallelism": "single GPU"},
+        "int8_TOPS_useful": 2 * total_macs / (ms_per_step * 1e-3) / 1e12,
+        "int8_TOPS_frac_of_peak": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+        "roofline": roofline, "stages": stages, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -59,10 +59,11 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
   return p;
 }
 
-enum class Kernel { Generic, DwMfma, GemmMfma };
+enum class Kernel { Generic, DwMfma, GemmMfma, PwMfma };
 
 Kernel pick_kernel(const ConvParams& p) {
   if (p.depthwise) return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
+  if (qasr::pw_mfma_supported(p)) return Kernel::PwMfma;
   if ((p.k == 1 || p.w_packed) && qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
   return Kernel::Generic;
 }
@@ -71,6 +72,7 @@ const char* kernel_name(Kernel k) {
   switch (k) {
     case Kernel::DwMfma: return "dw_mfma";
     case Kernel::GemmMfma: return "gemm_mfma";
+    case Kernel::PwMfma: return "pw_mfma";
     default: return "conv_generic";
   }
 }
@@ -80,6 +82,7 @@ qasr_status launch(const ConvParams& p, hipStream_t st) {
   switch (pick_kernel(p)) {
     case Kernel::DwMfma: e = qasr::launch_dw_mfma(p, st); break;
     case Kernel::GemmMfma: e = qasr::launch_gemm_mfma(p, st); break;
+    case Kernel::PwMfma: e = qasr::launch_pw_mfma(p, st); break;
     default: e = qasr::launch_conv_generic(p, st); break;
   }
   return hip_status(e);

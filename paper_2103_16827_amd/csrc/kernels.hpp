@@ -25,4 +25,8 @@ hipError_t launch_dw_mfma(const ConvParams& p, hipStream_t st);
 bool gemm_mfma_supported(const ConvParams& p);
 hipError_t launch_gemm_mfma(const ConvParams& p, hipStream_t st);
 
+// Pointwise convolution (k = 1) with LDS transpose reads; needs 16-byte aligned frame rows.
+bool pw_mfma_supported(const ConvParams& p);
+hipError_t launch_pw_mfma(const ConvParams& p, hipStream_t st);
+
 }  // namespace qasr

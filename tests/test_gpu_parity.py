@@ -163,7 +163,8 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
         for o in net.ops:
             flags = Q.FLAG_W_PACKED if (not o.depthwise and o.k > 1) else 0
             name = Q.conv1d_kernel_name(desc_of(o, net.B, flags))
-            assert name == ("dw_mfma" if o.depthwise else "gemm_mfma"), (cfg, o.name, name)
+            want = "dw_mfma" if o.depthwise else ("pw_mfma" if o.k == 1 and o.Tin % 16 == 0 else "gemm_mfma")
+            assert name == want, (cfg, o.name, name)
 
 
 # ----------------------------------------------------------------------------- encoders
