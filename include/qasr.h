@@ -80,14 +80,13 @@ int32_t qasr_conv1d_out_len(const qasr_conv1d_desc* d);
  * BatchNorm bias, integer ReLU; dyadic rescale and residual as stated above).
  *   x        [B,Cin,Tin]  int8 device (batch stride x_batch_stride)
  *   w        [Cout,Cin/groups,k] int8 device; with QASR_FLAG_W_PACKED the buffer written by
- *            qasr_pack_weights (only meaningful for groups == 1 and k > 1; otherwise the
- *            packed form is the plain form)
+ *            qasr_pack_weights for this descriptor
  *   bias     [Cout] int32 device, or NULL for 0
  *   m, s     [Cout] int32 device
  *   residual [B,Cout,Tout] int8 device or NULL
  *   y        [B,Cout,Tout] int8 device (batch stride y_batch_stride)
- * Dense convolutions with k > 1 run fastest with packed weights; with plain weights a slower
- * kernel is used.  Asynchronous on `stream`. */
+ * Pointwise and dense layers run fastest with packed weights; plain weights take slower loads
+ * (k == 1) or the generic kernel (k > 1).  Asynchronous on `stream`. */
 qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const int8_t* w,
                              const int32_t* bias, const int32_t* m, const int32_t* s,
                              const int8_t* residual, int8_t* y, void* stream);
@@ -95,10 +94,13 @@ qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const i
 /* Size in bytes of the packed form of a layer's weights (0 on an invalid descriptor). */
 size_t qasr_packed_weight_bytes(const qasr_conv1d_desc* d);
 
-/* Re-orders w [Cout,Cin,k] into the tap-major form [k][Cout][Cin] that the implicit-GEMM
- * kernel consumes with 16-byte operand loads.  Weights are fixed at inference (Sec. 2.1,
- * static quantisation), so this runs once per layer.  w_packed: device, caller-owned,
- * qasr_packed_weight_bytes(d) bytes, 16-byte aligned.  Asynchronous on `stream`. */
+/* Re-orders w [Cout,Cin,k] of a groups == 1 layer with Cin % 64 == 0 into the matrix-core operand
+ * order [k][ceil(Cout/16)][Cin/64][64 lanes][16 bytes] (lane 16*gi + n of a block holds output
+ * channel 16*co16 + n and input channels 64*kc + 8*gi + 0..7 and 64*kc + 32 + 8*gi + 0..7; rows
+ * beyond Cout are zero), so that every wave-wide operand load is 1 KiB of contiguous memory.
+ * For every other layer the packed form is the plain form (a copy).  Weights are fixed at
+ * inference (Sec. 2.1, static quantisation), so this runs once per layer.  w_packed: device,
+ * caller-owned, qasr_packed_weight_bytes(d) bytes, 16-byte aligned.  Asynchronous on `stream`. */
 qasr_status qasr_pack_weights(const qasr_conv1d_desc* d, const int8_t* w, int8_t* w_packed,
                               void* stream);
 
@@ -128,7 +130,7 @@ typedef struct {
 typedef struct qasr_encoder qasr_encoder; /* opaque host object */
 
 /* Validates the op list (shapes chain through the slots, no op writes a slot it reads, slot 0
- * is never written), sizes the slots, and packs dense k > 1 weights once into device memory
+ * is never written), sizes the slots, and packs the groups == 1 weights once into device memory
  * owned by the encoder (the only device allocation the library ever makes; it synchronises
  * `stream`-independent, i.e. it blocks until packing is done).  *out is set on QASR_OK. */
 qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slots,

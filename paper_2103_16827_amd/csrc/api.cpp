@@ -20,6 +20,15 @@ qasr_status hip_status(hipError_t e) {
 
 constexpr uint32_t kKnownFlags = QASR_FLAG_RELU | QASR_FLAG_W_PACKED;
 
+// Weights have a packed form only for groups == 1 with Cin a multiple of 64 (the matrix-core
+// kernels' operand order); otherwise "packed" is the plain order.
+bool has_packed_form(const qasr_conv1d_desc* d) { return d->groups == 1 && d->Cin % 64 == 0; }
+
+size_t packed_bytes_of(const qasr_conv1d_desc* d) {
+  if (!has_packed_form(d)) return (size_t)((int64_t)d->Cout * (d->groups != 1 ? 1 : d->Cin) * d->k);
+  return (size_t)((int64_t)d->k * ((d->Cout + 15) / 16) * 16 * d->Cin);
+}
+
 int64_t out_len64(const qasr_conv1d_desc* d) {
   const int64_t span = (int64_t)d->Tin + d->pad_left + d->pad_right - (int64_t)d->dilation * (d->k - 1) - 1;
   return span < 0 ? 0 : span / d->stride + 1;
@@ -53,7 +62,7 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
   p.k = d->k; p.stride = d->stride; p.dil = d->dilation; p.pl = d->pad_left;
   p.depthwise = d->groups != 1;
   p.relu = (d->flags & QASR_FLAG_RELU) ? 1 : 0;
-  p.w_packed = (!p.depthwise && d->k > 1 && (d->flags & QASR_FLAG_W_PACKED)) ? 1 : 0;
+  p.w_packed = (has_packed_form(d) && (d->flags & QASR_FLAG_W_PACKED)) ? 1 : 0;
   p.xbs = d->x_batch_stride ? d->x_batch_stride : (int64_t)d->Cin * d->Tin;
   p.ybs = d->y_batch_stride ? d->y_batch_stride : (int64_t)d->Cout * p.Tout;
   return p;
@@ -64,7 +73,7 @@ enum class Kernel { Generic, DwMfma, GemmMfma, PwMfma };
 Kernel pick_kernel(const ConvParams& p) {
   if (p.depthwise) return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
   if (qasr::pw_mfma_supported(p)) return Kernel::PwMfma;
-  if ((p.k == 1 || p.w_packed) && qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
+  if (qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
   return Kernel::Generic;
 }
 
@@ -102,7 +111,7 @@ struct qasr_encoder {
   std::vector<Op> ops;
   std::vector<size_t> slot_off;   // byte offset of slot i in the workspace (slot 0 unused)
   size_t ws_bytes = 0;
-  int8_t* packed = nullptr;       // device: packed weights of all dense k>1 layers
+  int8_t* packed = nullptr;       // device: packed weights of all groups == 1 layers
 };
 
 extern "C" {
@@ -134,18 +143,18 @@ qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const i
 
 size_t qasr_packed_weight_bytes(const qasr_conv1d_desc* d) {
   if (check_desc(d) != QASR_OK) return 0;
-  const int64_t cin_g = d->groups != 1 ? 1 : d->Cin;
-  return (size_t)((int64_t)d->Cout * cin_g * d->k);
+  return packed_bytes_of(d);
 }
 
 qasr_status qasr_pack_weights(const qasr_conv1d_desc* d, const int8_t* w, int8_t* w_packed, void* stream) {
   const qasr_status st = check_desc(d);
   if (st != QASR_OK) return st;
   if (!w || !w_packed) return QASR_ERR_NULL;
-  const size_t n = qasr_packed_weight_bytes(d);
-  if (overlaps(w, (int64_t)n, w_packed, (int64_t)n)) return QASR_ERR_ALIAS;
+  const size_t n = packed_bytes_of(d);
+  const int64_t n_plain = (int64_t)d->Cout * (d->groups != 1 ? 1 : d->Cin) * d->k;
+  if (overlaps(w, n_plain, w_packed, (int64_t)n)) return QASR_ERR_ALIAS;
   hipError_t e;
-  if (d->groups != 1 || d->k == 1)   // packed form == plain form
+  if (!has_packed_form(d))   // packed form == plain form
     e = hipMemcpyAsync(w_packed, w, n, hipMemcpyDeviceToDevice, (hipStream_t)stream);
   else
     e = qasr::launch_pack_weights(w, w_packed, d->Cout, d->Cin, d->k, (hipStream_t)stream);
@@ -208,7 +217,7 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     slot[o.out_slot].T = Tout;
     const size_t bytes = (size_t)o.d.B * o.d.Cout * Tout;
     if (bytes > slot_bytes[o.out_slot]) slot_bytes[o.out_slot] = bytes;
-    if (o.d.groups == 1 && o.d.k > 1) packed_bytes += round256((size_t)o.d.Cout * o.d.Cin * o.d.k);
+    if (has_packed_form(&o.d)) packed_bytes += round256(packed_bytes_of(&o.d));
   }
 
   qasr_encoder* e = new (std::nothrow) qasr_encoder();
@@ -234,9 +243,9 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     op.d = o.d;
     op.in_slot = o.in_slot; op.res_slot = o.res_slot; op.out_slot = o.out_slot;
     const int8_t* w = o.w;
-    if (o.d.groups == 1 && o.d.k > 1) {
+    if (has_packed_form(&o.d)) {
       int8_t* wp = e->packed + poff;
-      poff += round256((size_t)o.d.Cout * o.d.Cin * o.d.k);
+      poff += round256(packed_bytes_of(&o.d));
       const hipError_t pe = qasr::launch_pack_weights(o.w, wp, o.d.Cout, o.d.Cin, o.d.k, nullptr);
       if (pe != hipSuccess) {
         qasr_encoder_destroy(e);

@@ -19,8 +19,23 @@ struct ConvParams {
   int32_t k, stride, dil, pl;
   int32_t depthwise;     // 0: groups == 1, 1: groups == Cin == Cout
   int32_t relu;
-  int32_t w_packed;      // dense k>1 weights are [k][Cout][Cin] instead of [Cout][Cin][k]
+  int32_t w_packed;      // groups == 1, Cin % 64 == 0: weights are in MFMA operand order (below)
 };
+
+// Packed weight layout (groups == 1, Cin % 64 == 0): [k][ceil(Cout/16)][Cin/64][64 lanes][16 bytes].
+// Lane l = 16*gi + n of block (j, co16, kc) holds output channel co = 16*co16 + n (zeros beyond
+// Cout) and, in its bytes e = 0..15, the input channels
+//     ci = 64*kc + 8*gi + e            (e < 8)
+//     ci = 64*kc + 32 + 8*gi + (e - 8) (e >= 8)
+// which is the order in which the activation operand of the matrix-core kernels is assembled.
+// One wave-wide 16-byte load of a block is 1 KiB of contiguous memory.
+__host__ __device__ inline int64_t packed_weight_index(int j, int co, int ci, int Cout, int Cin) {
+  const int co16n = (Cout + 15) >> 4, kch = Cin >> 6;
+  const int kc = ci >> 6, r = ci & 63;
+  const int gi = (r & 31) >> 3, e = (r & 7) + ((r >> 5) << 3);
+  const int lane = gi * 16 + (co & 15);
+  return ((((int64_t)j * co16n + (co >> 4)) * kch + kc) * 64 + lane) * 16 + e;
+}
 
 // Dyadic rescale v = floor((A*m + 2^(s-1)) / 2^s), 0 <= m < 2^31, 1 <= s <= 62, returned
 // clamped to [-2^20, 2^20] (the caller adds an int8 residual and clamps to int8 next, so any

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(256) void conv_generic_kernel(ConvParams p) {
       for (int j = 0; j < p.k; ++j) {
         const int ti = t0 + j * p.dil;
         if (ti >= 0 && ti < p.Tin) {
-          const int64_t wi = p.w_packed ? ((int64_t)j * p.Cout + co) * p.Cin + ci
+          const int64_t wi = p.w_packed ? packed_weight_index(j, co, ci, p.Cout, p.Cin)
                                         : ((int64_t)co * p.Cin + ci) * p.k + j;
           A += (int32_t)xr[ti] * (int32_t)p.w[wi];
         }
@@ -49,20 +49,28 @@ hipError_t launch_conv_generic(const ConvParams& p, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------ weight re-ordering
+// [Cout][Cin][k] -> MFMA operand order (see packed_weight_index); one thread per packed byte.
 __global__ __launch_bounds__(256) void pack_weights_kernel(const int8_t* __restrict__ w,
                                                           int8_t* __restrict__ wp, int Cout,
                                                           int Cin, int k) {
-  const int64_t total = (int64_t)Cout * Cin * k;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // over the packed order
+  const int co16n = (Cout + 15) >> 4, kch = Cin >> 6;
+  const int64_t total = (int64_t)k * co16n * kch * 1024;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= total) return;
-  const int ci = (int)(idx % Cin);
-  const int co = (int)((idx / Cin) % Cout);
-  const int j = (int)(idx / ((int64_t)Cin * Cout));
-  wp[idx] = w[((int64_t)co * Cin + ci) * k + j];
+  const int e = (int)(idx & 15), lane = (int)((idx >> 4) & 63);
+  int64_t rest = idx >> 10;
+  const int kc = (int)(rest % kch);
+  rest /= kch;
+  const int co16 = (int)(rest % co16n);
+  const int j = (int)(rest / co16n);
+  const int n = lane & 15, gi = lane >> 4;
+  const int co = 16 * co16 + n;
+  const int ci = 64 * kc + (e < 8 ? 8 * gi + e : 32 + 8 * gi + (e - 8));
+  wp[idx] = co < Cout ? w[((int64_t)co * Cin + ci) * k + j] : (int8_t)0;
 }
 
 hipError_t launch_pack_weights(const int8_t* w, int8_t* wp, int Cout, int Cin, int k, hipStream_t st) {
-  const int64_t total = (int64_t)Cout * Cin * k;
+  const int64_t total = (int64_t)k * ((Cout + 15) / 16) * (Cin / 64) * 1024;
   const int64_t blocks = (total + 255) / 256;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   return launch_kernel(pack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, st, w, wp, Cout, Cin, k);

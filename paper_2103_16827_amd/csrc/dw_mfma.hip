@@ -18,6 +18,9 @@
 // across row ends.
 #include "kernels.hpp"
 
+#include <cstdlib>
+#include <type_traits>
+
 namespace qasr {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -79,6 +82,10 @@ __global__ __launch_bounds__(256) void dw_mfma_kernel(ConvParams p, DwGeom g) {
     }
   }
 
+  // per-channel constants: uniform over the workgroup, requested before anything waits
+  const int32_t bias = p.bias ? p.bias[c] : 0;
+  const int32_t mc = p.m[c], sc = p.s[c];
+
   // ---- 2. Toeplitz operand: wrow[q] = w[j] where q - 15 - delta == j * dilation
   for (int q = tid; q < 64 * KC + 16; q += 256) {
     const int rel = q - 15 - g.delta;
@@ -119,60 +126,73 @@ __global__ __launch_bounds__(256) void dw_mfma_kernel(ConvParams p, DwGeom g) {
 #pragma unroll
   for (int kc = 0; kc < KC; ++kc) a[kc] = *reinterpret_cast<const v4i*>(a_lds + kc * 1024 + lane * 16);
 
-  const int32_t bias = p.bias ? p.bias[c] : 0;
-  const int32_t mc = p.m[c], sc = p.s[c];
+  // groups per strip: all strips of a wave have the same count (R > 1 only when nseg == 1)
+  const int b0 = strip0 / g.nseg;
+  const int T0w = (strip0 - b0 * g.nseg) * kSeg;
+  const int G = (min(kSeg, p.Tout - T0w) + 15) >> 4;
+  const int ntiles = (Rv * G + 15) >> 4;
   const int lo = p.relu ? 0 : -128;
 
-  // groups per strip: all strips of a wave have the same count (R > 1 only when nseg == 1)
-  int T0w = 0;
-  if (g.nseg > 1) T0w = (strip0 % g.nseg) * kSeg;
-  const int G = (min(kSeg, p.Tout - T0w) + 15) >> 4;
-  const int ncols = Rv * G;
-  const int ntiles = (ncols + 15) >> 4;
+  // Output addressing: wave-uniform 64-bit base + a 32-bit per-lane offset.  Strip r of the wave is
+  // batch item b0 + r (nseg == 1) or the only strip (R == 1); the host keeps R * ybs below 2^31.
+  const int64_t obase = (int64_t)b0 * p.ybs + (int64_t)c * p.Tout + T0w;
+  int8_t* const yb = p.y + obase;
+  const int8_t* const rb = p.res ? p.res + obase : nullptr;
+  const int strip_pitch = g.nseg == 1 ? (int)p.ybs : 0;
+  const int Tleft = p.Tout - T0w;                     // frames of this strip from its first frame
 
-  for (int tile = 0; tile < ntiles; ++tile) {
-    const int q = 16 * tile + n;
-    const bool valid = q < ncols;
-    const int qc = valid ? q : 0;
-    int r = 0;
+  // column walk: lane n starts at column n of strip 0 and advances 16 columns per tile
+  int r = 0, grp = n;
+  while (grp >= G) { grp -= G; ++r; }
+
+  auto tile_loop = [&](auto fast_tag) {
+    constexpr bool FAST = decltype(fast_tag)::value;
+    const int sh = FAST ? sc - 32 : 0;
+    const int rnd = FAST ? 1 << (sc - 33) : 0;
+    for (int tile = 0; tile < ntiles; ++tile) {
+      const bool valid = r < Rv;
+      const int rr_ = valid ? r : 0;
+      const unsigned char* bp = my + ((rr_ * g.NCH + grp + gi) << 4);
+      v4i acc = {bias, bias, bias, bias};
 #pragma unroll
-    for (int j = 1; j < 8; ++j) r += (j < g.R && qc >= j * G) ? 1 : 0;
-    const int grp = qc - r * G;
-    const unsigned char* bp = my + ((size_t)r * g.NCH + grp + gi) * 16;
-    v4i acc = {bias, bias, bias, bias};
+      for (int kc = 0; kc < KC; ++kc) {
+        const v4i xb = *reinterpret_cast<const v4i*>(bp + kc * 64);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[kc], xb, acc, 0, 0, 0);
+      }
+      const int t = 16 * grp + 4 * gi;                // frame inside the strip
+      if (valid && t < Tleft) {
+        const int o = rr_ * strip_pitch + t;
+        int32_t v[4];
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-      const v4i xb = *reinterpret_cast<const v4i*>(bp + kc * 64);
-      acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[kc], xb, acc, 0, 0, 0);
-    }
-    // lane (n, gi) holds frames t .. t+3 of column q
-    const int strip = strip0 + r;
-    const int b = strip / g.nseg;
-    const int t = (strip - b * g.nseg) * kSeg + 16 * grp + 4 * gi;
-    if (valid && t < p.Tout) {
-      const int64_t o = (int64_t)b * p.ybs + (int64_t)c * p.Tout + t;
-      if (g.aligned_out) {
-        uint32_t rr = 0;
-        if (p.res) rr = *reinterpret_cast<const uint32_t*>(p.res + o);
-        uint32_t pk = 0;
+        for (int i = 0; i < 4; ++i)
+          v[i] = FAST ? ((int32_t)__mulhi(acc[i], mc) + rnd) >> sh : dyadic_rescale(acc[i], mc, sc);
+        if (g.aligned_out) {
+          if (rb) {
+            const uint32_t rw = *reinterpret_cast<const uint32_t*>(rb + o);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          int32_t v = dyadic_rescale(acc[i], mc, sc) + (int32_t)(int8_t)(rr >> (8 * i));
-          pk |= (uint32_t)(clamp_i8(v, lo) & 0xff) << (8 * i);
-        }
-        *reinterpret_cast<uint32_t*>(p.y + o) = pk;
-      } else {
+            for (int i = 0; i < 4; ++i) v[i] += (int32_t)(int8_t)(rw >> (8 * i));
+          }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          if (t + i < p.Tout) {
-            int32_t v = dyadic_rescale(acc[i], mc, sc);
-            if (p.res) v += (int32_t)p.res[o + i];
-            p.y[o + i] = (int8_t)clamp_i8(v, lo);
+          for (int i = 0; i < 4; ++i) v[i] = clamp_i8(v[i], lo);
+          const uint32_t p01 = __builtin_amdgcn_perm((uint32_t)v[1], (uint32_t)v[0], 0x0c0c0400u);
+          const uint32_t p23 = __builtin_amdgcn_perm((uint32_t)v[3], (uint32_t)v[2], 0x04000c0cu);
+          *reinterpret_cast<uint32_t*>(yb + o) = p01 | p23;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (t + i < Tleft) {
+              int32_t w_ = v[i];
+              if (rb) w_ += (int32_t)rb[o + i];
+              yb[o + i] = (int8_t)clamp_i8(w_, lo);
+            }
           }
         }
       }
+      grp += 16;
+      while (grp >= G) { grp -= G; ++r; }
     }
-  }
+  };
+  if (sc >= 33) tile_loop(std::true_type{}); else tile_loop(std::false_type{});
 }
 
 bool geometry(const ConvParams& p, DwGeom& g, int& KC) {
@@ -193,7 +213,7 @@ bool geometry(const ConvParams& p, DwGeom& g, int& KC) {
   g.R = 1;
   if (g.nseg == 1) {
     double best = -1.0;
-    for (int R = 1; R <= 8 / g.NI && R <= p.B; R *= 2) {
+    for (int R = 1; R <= 8 / g.NI && R <= p.B && (int64_t)R * p.ybs < 0x7fffffffLL; R *= 2) {
       const int cols = R * Gfull;
       const double eff = (double)cols / (16.0 * ((cols + 15) / 16));
       const double blocks = (double)p.Cout * ((p.B + 4 * R - 1) / (4 * R));
@@ -201,6 +221,12 @@ bool geometry(const ConvParams& p, DwGeom& g, int& KC) {
       const double score = eff * (0.25 + 0.75 * fill);
       if (score > best + 1e-9) { best = score; g.R = R; }
     }
+  }
+  if (const char* e = getenv("QASR_DW_R")) {             // tuning override: strips per wave
+    const int R = atoi(e);
+    if (g.nseg == 1 && (R == 1 || R == 2 || R == 4 || R == 8) && R * g.NI <= 8 &&
+        (int64_t)R * p.ybs < 0x7fffffffLL)
+      g.R = R;
   }
   const int64_t gy = (nstrips + 4 * g.R - 1) / (4 * g.R);
   if (gy > 65535) return false;

@@ -15,8 +15,10 @@
 // [frame][64 channels] rows (80-byte pitch, so that the 16-byte operand reads of 16 consecutive
 // frames hit distinct banks).  A tap is then just a row offset; the transposition is paid once
 // per chunk and amortised over the k taps.  Weights go straight from global memory / L2 to
-// registers in operand layout (tap-major packed form [k][Cout][Cin] for k > 1), prefetched one
-// tap ahead.
+// registers in operand layout (the packed form: 1 KiB contiguous per wave-wide load), prefetched
+// one tap ahead.  The packed form orders the 64 channels of a chunk so that lane group gi holds
+// channels 8 gi..+8 and 32 + 8 gi..+8; the LDS rows are written in the matching column order, so
+// that an operand is still one 16-byte read.
 #include "kernels.hpp"
 
 namespace qasr {
@@ -83,7 +85,21 @@ __global__ __launch_bounds__(256) void gemm_conv_kernel(ConvParams p, GemmGeom g
 
   const int nfq = g.rows >> 2;                      // frame quads per chunk
   const int nblk = 16 * nfq;                        // 4x4 blocks per chunk
-  const int64_t tap_pitch = (int64_t)p.Cout * p.Cin;
+
+  // weight operand of (tap j, chunk kc, column tile nt)
+  const int co16n = (p.Cout + 15) >> 4;
+  auto load_w = [&](int j, int kc, int nt) -> v4i {
+    if (p.w_packed) {
+      const int co16 = min((co_w >> 4) + nt, co16n - 1);
+      return *reinterpret_cast<const v4i*>(
+          p.w + ((((int64_t)j * co16n + co16) * g.kchunks + kc) * 64 + lane) * 16);
+    }
+    // plain [Cout][Cin] rows (k == 1 only): the two 8-byte pieces of the operand order
+    const int8_t* wp = p.w + (int64_t)co_ld[nt] * p.Cin + 64 * kc + 8 * gi;
+    const int2 w0 = *reinterpret_cast<const int2*>(wp);
+    const int2 w1 = *reinterpret_cast<const int2*>(wp + 32);
+    return (v4i){w0.x, w0.y, w1.x, w1.y};
+  };
 
   for (int kc = 0; kc < g.kchunks; ++kc) {
     // ---- activation chunk: [64 ci][rows frames] -> LDS [frame][64 ci]
@@ -98,17 +114,18 @@ __global__ __launch_bounds__(256) void gemm_conv_kernel(ConvParams p, GemmGeom g
       }
       uint32_t c[4];
       transpose4x4(r[0], r[1], r[2], r[3], c);
+      // channels 4 cq..+4 go to the column that the operand order assigns them
+      const int col = 16 * ((cq >> 1) & 3) + 8 * (cq >> 3) + 4 * (cq & 1);
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        *reinterpret_cast<uint32_t*>(xs + (4 * fq + e) * kXS + 4 * cq) = c[e];
+        *reinterpret_cast<uint32_t*>(xs + (4 * fq + e) * kXS + col) = c[e];
     }
     __syncthreads();
 
     // ---- taps: weights one tap ahead in registers
     v4i wb[2][NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-      wb[0][nt] = *reinterpret_cast<const v4i*>(p.w + (int64_t)co_ld[nt] * p.Cin + 64 * kc + 16 * gi);
+    for (int nt = 0; nt < NT; ++nt) wb[0][nt] = load_w(0, kc, nt);
     for (int j = 0; j < p.k; j += 2) {
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
@@ -116,9 +133,7 @@ __global__ __launch_bounds__(256) void gemm_conv_kernel(ConvParams p, GemmGeom g
         if (jj < p.k) {
           if (jj + 1 < p.k) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              wb[half ^ 1][nt] = *reinterpret_cast<const v4i*>(
-                  p.w + (jj + 1) * tap_pitch + (int64_t)co_ld[nt] * p.Cin + 64 * kc + 16 * gi);
+            for (int nt = 0; nt < NT; ++nt) wb[half ^ 1][nt] = load_w(jj + 1, kc, nt);
           }
           const unsigned char* arow = xs + (foff + jj * p.dil + n * p.stride) * kXS + 16 * gi;
 #pragma unroll

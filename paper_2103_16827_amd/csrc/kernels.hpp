@@ -14,7 +14,7 @@ hipError_t launch_requant(const int32_t* acc, int B, int C, int T, const int32_t
                           const int32_t* m, const int32_t* s, const int8_t* res, int relu,
                           int8_t* y, hipStream_t st);
 
-// [Cout][Cin][k] -> [k][Cout][Cin]
+// [Cout][Cin][k] -> MFMA operand order (common.hpp: packed_weight_index); needs Cin % 64 == 0
 hipError_t launch_pack_weights(const int8_t* w, int8_t* wp, int Cout, int Cin, int k, hipStream_t st);
 
 // Depthwise convolution as a banded-Toeplitz product on the int8 matrix cores (stride 1).

@@ -69,6 +69,9 @@ def test_null_and_alias_rejected_before_any_launch():
     assert L.qasr_pack_weights(ctypes.byref(d), None, f(64), None) == -1
     assert Q.packed_weight_bytes(d) == 4 * 4 * 3
     assert Q.packed_weight_bytes(make_desc(1, 4, 4, 10, k=3, groups=4)) == 4 * 3
+    # matrix-core operand order: Cout rounded up to 16 rows
+    assert Q.packed_weight_bytes(make_desc(1, 64, 29, 10, k=3)) == 3 * 32 * 64
+    assert Q.packed_weight_bytes(make_desc(1, 128, 32, 10)) == 32 * 128
 
 
 def _ops(specs):

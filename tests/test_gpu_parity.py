@@ -140,6 +140,13 @@ REAL = [
     dict(name="pw_T_not4", B=2, Cin=128, Cout=64, T=203, res=True),
     dict(name="pw_minus128", B=1, Cin=128, Cout=64, T=160, wmin=-128),
     dict(name="pw_generic_s", B=1, Cin=128, Cout=64, T=160, s_lo=20, s_hi=40),
+    dict(name="pw_512_512_packed", B=2, Cin=512, Cout=512, T=800, res=True, packed=True),
+    dict(name="pw_256_256_packed", B=1, Cin=256, Cout=256, T=800, packed=True),
+    dict(name="pw_1024_29_packed", B=2, Cin=1024, Cout=29, T=800, relu=False, packed=True),
+    dict(name="pw_2048_512_packed", B=1, Cin=2048, Cout=512, T=400, relu=False, packed=True),
+    dict(name="pw_192_200_packed_T333", B=3, Cin=192, Cout=200, T=333, res=True, packed=True),
+    dict(name="pw_320_72_packed_T332", B=2, Cin=320, Cout=72, T=332, res=True, packed=True),
+    dict(name="pw_64_64_packed_generic_s", B=1, Cin=64, Cout=64, T=160, s_lo=20, s_hi=40, packed=True),
     dict(name="c1_dense_s2", B=2, Cin=64, Cout=256, T=1600, k=33, stride=2, pad=(16, 16), packed=True),
     dict(name="c1_dense_s2_raw", B=1, Cin=64, Cout=256, T=400, k=33, stride=2, pad=(16, 16)),
     dict(name="jasper_k11", B=1, Cin=256, Cout=256, T=800, k=11, packed=True, res=True),
@@ -161,9 +168,9 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
     for cfg in range(5):
         net = W.build_config(cfg)
         for o in net.ops:
-            flags = Q.FLAG_W_PACKED if (not o.depthwise and o.k > 1) else 0
+            flags = 0 if o.depthwise else Q.FLAG_W_PACKED
             name = Q.conv1d_kernel_name(desc_of(o, net.B, flags))
-            want = "dw_mfma" if o.depthwise else ("pw_mfma" if o.k == 1 and o.Tin % 16 == 0 else "gemm_mfma")
+            want = "dw_mfma" if o.depthwise else ("pw_mfma" if o.k == 1 and o.Tin % 16 == 0 and o.Cin % 256 == 0 else "gemm_mfma")
             assert name == want, (cfg, o.name, name)
 
 
