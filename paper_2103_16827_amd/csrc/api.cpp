@@ -68,10 +68,11 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
   return p;
 }
 
-enum class Kernel { Generic, DwMfma, GemmMfma, PwMfma };
+enum class Kernel { Generic, DwMfma, GemmMfma, PwMfma, PwTile };
 
 Kernel pick_kernel(const ConvParams& p) {
   if (p.depthwise) return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
+  if (qasr::pw_tile_supported(p)) return Kernel::PwTile;
   if (qasr::pw_mfma_supported(p)) return Kernel::PwMfma;
   if (qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
   return Kernel::Generic;
@@ -82,6 +83,7 @@ const char* kernel_name(Kernel k) {
     case Kernel::DwMfma: return "dw_mfma";
     case Kernel::GemmMfma: return "gemm_mfma";
     case Kernel::PwMfma: return "pw_mfma";
+    case Kernel::PwTile: return "pw_tile";
     default: return "conv_generic";
   }
 }
@@ -92,6 +94,7 @@ qasr_status launch(const ConvParams& p, hipStream_t st) {
     case Kernel::DwMfma: e = qasr::launch_dw_mfma(p, st); break;
     case Kernel::GemmMfma: e = qasr::launch_gemm_mfma(p, st); break;
     case Kernel::PwMfma: e = qasr::launch_pw_mfma(p, st); break;
+    case Kernel::PwTile: e = qasr::launch_pw_tile(p, st); break;
     default: e = qasr::launch_conv_generic(p, st); break;
   }
   return hip_status(e);

@@ -72,4 +72,30 @@ __device__ __forceinline__ int32_t clamp_i8(int32_t v, int32_t lo) {
   return min(127, max(lo, v));
 }
 
+// median of three = clamp(x, lo, hi) for lo <= hi, in one instruction (the compiler only forms it
+// by itself when both bounds are compile-time constants)
+__device__ __forceinline__ int32_t med3_i32(int32_t x, int32_t lo, int32_t hi) {
+  int32_t r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(lo), "v"(hi));
+  return r;
+}
+
+// Epilogue of 4 accumulators of one channel (4 consecutive frames): dyadic rescale, residual bytes
+// of `resw` added (pass 0 for none), clamp to [lo, 127], packed little-endian into one dword.
+// FAST: s >= 33, sh = s - 32, rnd = 2^(s-33) (see dyadic_rescale); otherwise sh carries s itself.
+template <bool FAST, bool RES>
+__device__ __forceinline__ uint32_t requant_pack4(const int32_t (&a)[4], int32_t m, int32_t sh, int32_t rnd,
+                                                  uint32_t resw, int32_t lo, int32_t hi127) {
+  int32_t v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[i] = FAST ? ((int32_t)__mulhi(a[i], m) + rnd) >> sh : dyadic_rescale(a[i], m, sh);
+    if (RES) v[i] += (int32_t)(int8_t)(resw >> (8 * i));
+    v[i] = med3_i32(v[i], lo, hi127);
+  }
+  const uint32_t p01 = __builtin_amdgcn_perm((uint32_t)v[1], (uint32_t)v[0], 0x0c0c0400u);
+  const uint32_t p23 = __builtin_amdgcn_perm((uint32_t)v[3], (uint32_t)v[2], 0x04000c0cu);
+  return p01 | p23;
+}
+
 }  // namespace qasr

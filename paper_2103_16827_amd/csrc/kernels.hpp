@@ -29,4 +29,9 @@ hipError_t launch_gemm_mfma(const ConvParams& p, hipStream_t st);
 bool pw_mfma_supported(const ConvParams& p);
 hipError_t launch_pw_mfma(const ConvParams& p, hipStream_t st);
 
+// Pointwise convolution (k = 1), activation tile stationary in LDS (direct global->LDS loads);
+// needs packed weights, rows that are a multiple of 16 frames and Cin <= 1024.
+bool pw_tile_supported(const ConvParams& p);
+hipError_t launch_pw_tile(const ConvParams& p, hipStream_t st);
+
 }  // namespace qasr

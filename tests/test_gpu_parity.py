@@ -170,7 +170,14 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
         for o in net.ops:
             flags = 0 if o.depthwise else Q.FLAG_W_PACKED
             name = Q.conv1d_kernel_name(desc_of(o, net.B, flags))
-            want = "dw_mfma" if o.depthwise else ("pw_mfma" if o.k == 1 and o.Tin % 16 == 0 and o.Cin % 256 == 0 else "gemm_mfma")
+            if o.depthwise:
+                want = "dw_mfma"
+            elif o.k == 1 and o.Tin % 16 == 0 and o.Cin <= 1024:
+                want = "pw_tile"
+            elif o.k == 1 and o.Tin % 16 == 0 and o.Cin % 256 == 0:
+                want = "pw_mfma"
+            else:
+                want = "gemm_mfma"
             assert name == want, (cfg, o.name, name)
 
 
