@@ -57,6 +57,14 @@ __device__ __forceinline__ int32_t dyadic_rescale(int32_t A, int32_t m, int32_t 
   return (int32_t)v;
 }
 
+// The same rescale in its 64-bit form only (any 1 <= s <= 62), clamped like dyadic_rescale.
+__device__ __forceinline__ int32_t dyadic_rescale64(int32_t A, int32_t m, int32_t s) {
+  long long v = ((long long)A * (long long)m + (1ll << (s - 1))) >> s;
+  v = v > (1 << 20) ? (1 << 20) : v;
+  v = v < -(1 << 20) ? -(1 << 20) : v;
+  return (int32_t)v;
+}
+
 // Launch through hipLaunchKernel so that the status returned is this launch's own (the
 // thread-wide "last error" may hold a stale, unrelated value left by other HIP users).
 // Arguments are converted to the kernel's own parameter types before their addresses are taken.
@@ -89,7 +97,7 @@ __device__ __forceinline__ uint32_t requant_pack4(const int32_t (&a)[4], int32_t
   int32_t v[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    v[i] = FAST ? ((int32_t)__mulhi(a[i], m) + rnd) >> sh : dyadic_rescale(a[i], m, sh);
+    v[i] = FAST ? ((int32_t)__mulhi(a[i], m) + rnd) >> sh : dyadic_rescale64(a[i], m, sh);
     if (RES) v[i] += (int32_t)(int8_t)(resw >> (8 * i));
     v[i] = med3_i32(v[i], lo, hi127);
   }

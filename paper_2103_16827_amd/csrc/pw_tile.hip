@@ -43,6 +43,7 @@ struct PwtGeom {
   int kch;      // Cin / 64
   int passes;   // ceil(Cout / (128 * NT))
   int co16n;    // ceil(Cout / 16)
+  int tiles, tiles_per_xcd;
   int dbg;      // tuning: 1 skip activation loads, 2 skip multiply loop, 4 skip epilogue
 };
 
@@ -60,123 +61,195 @@ __device__ __forceinline__ void direct_load16(const void* gptr, const unsigned c
                :: "v"(gptr), "s"(m0v) : "memory");
 }
 
+// Global loads whose completion the kernel waits for by hand (wait_vm / tie below).  The
+// compiler does not know that the result is still in flight, so every use has to come after a
+// tie() that follows the wait.
+__device__ __forceinline__ v4i gload16(const void* p) {
+  v4i r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  return r;
+}
+// same, through a raw buffer resource: address = base + voff (per lane) + soff (wave-uniform)
+__device__ __forceinline__ v4i bload16(v4i rsrc, uint32_t voff, uint32_t soff) {
+  v4i r;
+  asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(r) : "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+  return r;
+}
+__device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t a = (uint64_t)(uintptr_t)base;
+  return (v4i){(int)(uint32_t)a, (int)(uint32_t)((a >> 32) & 0xffffu), (int)bytes, 0x00027000};
+}
+__device__ __forceinline__ int32_t gload4(const void* p) {
+  int32_t r;
+  asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  return r;
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+// at most n vector-memory operations outstanding (n wave-uniform); anything above 24 waits for all
+__device__ __forceinline__ void wait_vm_dyn(int n) {
+  switch (n) {
+#define QASR_W(N) case N: wait_vm<N>(); break;
+    QASR_W(1) QASR_W(2) QASR_W(3) QASR_W(4) QASR_W(5) QASR_W(6) QASR_W(7) QASR_W(8)
+    QASR_W(9) QASR_W(10) QASR_W(11) QASR_W(12) QASR_W(13) QASR_W(14) QASR_W(15) QASR_W(16)
+    QASR_W(17) QASR_W(18) QASR_W(19) QASR_W(20) QASR_W(21) QASR_W(22) QASR_W(23) QASR_W(24)
+#undef QASR_W
+    default: wait_vm<0>(); break;
+  }
+}
+// makes every later use of v depend on this point of the (volatile-ordered) instruction stream
+__device__ __forceinline__ void tie(v4i& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void tie(int32_t& v) { asm volatile("" : "+v"(v)); }
+
+// Order of the vector-memory requests of a wave and the waits that follow from it (requests
+// complete in order, so "at most N outstanding" means everything but the N youngest is done):
+//
+//   R        residual tile of pass 0 -> staging (direct)            oldest
+//   C        bias, m, s of pass 0
+//   W(0)     weights of chunk 0                      (NT requests)
+//   X(0)     this wave's 8 rows of activation chunk 0 (direct, 1 request)
+//   W(1)
+//   X(1) .. X(kch-1)
+//   then, after chunk q has been multiplied:  W(q+2)  (the weight stream runs on across passes)
+//
+//   chunk 0 needs C, W(0), X(0):  NT + kch - 1 younger requests may stay outstanding
+//   chunk 1 needs W(1), X(1):     NT + kch - 2
+//   chunk q >= 2 needs W(q):      NT          (W(q) is younger than every X: all of X has landed)
+//
+// A workgroup barrier after each of the first three waits publishes the other waves' rows.  So
+// the multiplication starts as soon as the first 64 channels are there and the rest of the tile
+// streams in behind it.  Later passes (Cout > 128 NT) start from a full wait.
 template <int MT, int NT>
 __global__ __launch_bounds__(512) void pw_tile_kernel(ConvParams p, PwtGeom g) {
-  extern __shared__ __align__(16) unsigned char xs[];   // [Cin][128], slots swizzled
+  extern __shared__ __align__(128) unsigned char xs[];  // [Cin][128] slots swizzled, then staging
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, gi = lane >> 4;
-  const int g0 = blockIdx.x * MT;
+  // Workgroup -> tile: the hardware deals consecutive workgroups round-robin to the 8 XCDs (each
+  // with its own L2).  Neighbouring tiles share the cache lines at their common edge (a tile row is
+  // 16*MT bytes at an arbitrary 16-byte offset), so each XCD gets one contiguous range of tiles:
+  // the shared lines are then fetched once and written back whole.
+  const int tile = (int)(blockIdx.x & 7) * g.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= (unsigned)g.tiles_per_xcd || tile >= g.tiles) return;   // whole workgroup
+  const int g0 = tile * MT;
+  const int kch = g.kch;
 
-  // ---- 1. activation tile: lane -> (row 8 wave + lane/8 of each chunk, slot lane%8).  The unit
-  // a lane handles, u = slot ^ (row & 7), is the same for every row block of 8, so the same
-  // lane -> unit map serves the residual loads and the output stores of the staging area.
+  // lane -> (row lane/8 of a block of 8 rows, slot lane%8); the unit in that slot, slot ^ (row & 7),
+  // is the same for every block of 8 rows, so one lane -> unit map serves the activation loads,
+  // the residual loads and the output stores.
   const int u_l = (lane & 7) ^ (lane >> 3);
   const int gq_l = g0 + u_l;
   const bool u_ok = u_l < MT && gq_l < g.G;
   const int b_l = gq_l / g.gpr, t16_l = gq_l - b_l * g.gpr;
-  if (u_ok && !(g.dbg & 1)) {
-    const int r = 8 * wave + (lane >> 3);
-    const int8_t* src = p.x + (int64_t)b_l * p.xbs + (int64_t)r * p.Tin + 16 * t16_l;
-    const int64_t step = (int64_t)64 * p.Tin;
-    unsigned char* dst = xs + 8 * wave * 128;
-    for (int kc = 0; kc < g.kch; ++kc) {
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(src + kc * step),
-          (__attribute__((address_space(3))) void*)(dst + kc * 8192), 16, 0, 0);
-    }
-  }
   const int64_t yoff_l = (int64_t)b_l * p.ybs + 16 * t16_l;       // of this lane's unit
   unsigned char* const stage = xs + (size_t)p.Cin * 128 + wave * (16 * NT * 128);
+  int32_t* const stash = reinterpret_cast<int32_t*>(xs + (size_t)p.Cin * 128 + 8 * (16 * NT * 128)) + wave * (2 * NT * 64);
 
-  // ---- 2. per-lane constants of the transpose reads and of the output rows
-  const int l16 = lane & 15, j = l16 >> 1;
-  const unsigned char* abase = xs + (8 * gi + j) * 128 + 8 * (l16 & 1);
-  int aoff[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) aoff[mt] = (mt ^ j) << 4;
-
-  // staging address of this lane's accumulator dwords: row 16 nt + n, slot mt ^ (n & 7), + 4 gi
-  int soff[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) soff[mt] = n * 128 + ((mt ^ (n & 7)) << 4) + 4 * gi;
-
-  const int lo = p.relu ? 0 : -128;
-  const int64_t wlane = (int64_t)lane * 16;
-
-  auto w_ptr = [&](int ps, int nt) {
-    const int co16 = min((ps * 8 + wave) * NT + nt, g.co16n - 1);
-    return p.w + (int64_t)co16 * g.kch * 1024 + wlane;
-  };
-
-  // Residual tile of one pass -> staging area, by direct loads.  Issued through inline assembly:
-  // the compiler then keeps its load counters exact for the weight prefetches of the multiply
-  // loop (it cannot see these requests, which only makes its own waits stricter, never weaker);
-  // the epilogue waits for them explicitly.
   auto load_residual = [&](int co_w) {
     if (p.res && u_ok) {
 #pragma unroll
       for (int it = 0; it < 2 * NT; ++it) {
         const int co = co_w + 8 * it + (lane >> 3);
-        if (co < p.Cout)
-          direct_load16(p.res + yoff_l + (int64_t)co * p.Tout, stage + it * 1024);
+        if (co < p.Cout) direct_load16(p.res + yoff_l + (int64_t)co * p.Tout, stage + it * 1024);
       }
     }
   };
-  load_residual(wave * 16 * NT);
-
-  __builtin_amdgcn_s_waitcnt(0);   // all of this wave's direct loads have landed in LDS
-  __syncthreads();
-
-  for (int ps = 0; ps < g.passes; ++ps) {
-    const int co_w = (ps * 8 + wave) * 16 * NT;       // wave-uniform
-    if (co_w >= p.Cout) break;
-
-    const int8_t* wp[NT];
-    int32_t mc[NT], sc[NT];
-    v4i acc[MT][NT];
+  int32_t bv[NT], mc[NT], sc[NT];
+  auto load_consts = [&](int co_w) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      wp[nt] = w_ptr(ps, nt);
       const int co = min(co_w + 16 * nt + n, p.Cout - 1);
-      const int32_t bv = p.bias ? p.bias[co] : 0;
-      mc[nt] = p.m[co];
-      sc[nt] = p.s[co];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = (v4i){bv, bv, bv, bv};
+      bv[nt] = p.bias ? gload4(p.bias + co) : 0;
+      mc[nt] = gload4(p.m + co);
+      sc[nt] = gload4(p.s + co);
     }
-
-    if (ps > 0) load_residual(co_w);   // pass 0: requested together with the activation tile
-
-    // Software pipeline: the weights of chunk kk + 1 are requested before chunk kk is multiplied,
-    // and the activation operand of the next 16-frame group is read from LDS while the current
-    // one is multiplied.  The scheduling fences keep the compiler from sinking the requests
-    // down to their first use.
-    v4i wb[2][NT];
+  };
+  // weight stream: chunk q of the flat (pass, chunk) sequence, clamped at its end
+  const int Q = g.passes * kch;
+  const v4i wrsrc = make_rsrc(p.w, (uint32_t)g.co16n * (uint32_t)kch * 1024u);
+  const uint32_t wlane = (uint32_t)lane * 16;
+  auto load_w = [&](int q, v4i (&dst)[NT]) {
+    q = min(q, Q - 1);
+    const int ps = q / kch, kc = q - ps * kch;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) wb[0][nt] = *reinterpret_cast<const v4i*>(wp[nt]);
-    v2i a0 = lds_read_tr8(abase + aoff[0]);
-    v2i a1 = lds_read_tr8(abase + aoff[0] + 4096);
+    for (int nt = 0; nt < NT; ++nt) {
+      const int co16 = min((ps * 8 + wave) * NT + nt, g.co16n - 1);
+      dst[nt] = bload16(wrsrc, wlane, (uint32_t)(co16 * kch + kc) * 1024u);
+    }
+  };
 
-    for (int kc = 0; kc < ((g.dbg & 2) ? 0 : g.kch); kc += 2) {
+  v4i wb[2][NT];
+  load_residual(wave * 16 * NT);
+  load_consts(wave * 16 * NT);
+  {
+    const int r = 8 * wave + (lane >> 3);
+    const int8_t* src = p.x + (int64_t)b_l * p.xbs + (int64_t)r * p.Tin + 16 * t16_l;
+    const int64_t step = (int64_t)64 * p.Tin;
+    unsigned char* dst = xs + 8 * wave * 128;
+    load_w(0, wb[0]);
+    if (u_ok) direct_load16(src, dst);
+    load_w(1, wb[1]);
+    for (int kc = 1; kc < kch; ++kc)
+      if (u_ok) direct_load16(src + kc * step, dst + kc * 8192);
+  }
+
+  // per-lane constants of the transpose reads and of the staging writes
+  const int l16 = lane & 15, j = l16 >> 1;
+  // Slot of unit mt in row r is mt ^ (r & 7): with the row's own (r & 7) << 4 folded into the
+  // lane's base offset, the address of unit mt is base ^ (mt << 4)  (LDS tile is 128-byte aligned).
+  const uint32_t abase = (uint32_t)((8 * gi + j) * 128 + 8 * (l16 & 1)) | (uint32_t)(j << 4);
+  const uint32_t sbase = (uint32_t)(n * 128 + 4 * gi) | (uint32_t)((n & 7) << 4);   // staging row 16 nt + n
+  const int lo = p.relu ? 0 : -128;
+
+  int q = 0;
+  for (int ps = 0; ps < g.passes; ++ps) {
+    const int co_w = (ps * 8 + wave) * 16 * NT;       // wave-uniform
+    const bool active = co_w < p.Cout;                // idle waves still load and synchronise
+    if (ps > 0) {
+      load_residual(co_w);
+      load_consts(co_w);
+      wait_vm<0>();
+    }
+    v4i acc[MT][NT];
+
+    for (int kc = 0; kc < kch; kc += 2) {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const int kk = kc + h;
-        if (kk < g.kch) {
-          const int kn = min(kk + 1, g.kch - 1);
+        const int kk = kc + h;                        // kch is even
+        if (ps == 0 && kk < 2) {
+          wait_vm_dyn(NT + kch - 1 - kk);
+        } else if (!(ps > 0 && kk == 0)) {
+          wait_vm<NT>();
+        }
 #pragma unroll
-          for (int nt = 0; nt < NT; ++nt)
-            wb[h ^ 1][nt] = *reinterpret_cast<const v4i*>(wp[nt] + (int64_t)kn * 1024);
-          __builtin_amdgcn_sched_barrier(0);
-          const unsigned char* ab = abase + kk * 8192;
-          const unsigned char* abn = abase + kn * 8192;
+        for (int nt = 0; nt < NT; ++nt) tie(wb[h][nt]);
+        if (ps == 0 && kk <= 2) __syncthreads();
+        if (kk == 0) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            tie(bv[nt]); tie(mc[nt]); tie(sc[nt]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][nt] = (v4i){bv[nt], bv[nt], bv[nt], bv[nt]};
+            stash[(2 * nt) * 64 + lane] = mc[nt];       // parked in LDS until the epilogue
+            stash[(2 * nt + 1) * 64 + lane] = sc[nt];
+          }
+        }
+        if (active && !(g.dbg & 2)) {
+          // the activation operand of the next 16-frame group is read from LDS while the current
+          // one is multiplied; the scheduling fences keep that order
+          const unsigned char* ab = xs + kk * 8192;
+          v2i a0 = lds_read_tr8(ab + abase);
+          v2i a1 = lds_read_tr8(ab + abase + 4096);
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
             const v4i a = {a0.x, a0.y, a1.x, a1.y};
-            const unsigned char* nx = (mt + 1 < MT) ? ab + aoff[mt + 1] : abn + aoff[0];
-            a0 = lds_read_tr8(nx);
-            a1 = lds_read_tr8(nx + 4096);
+            if (mt + 1 < MT) {
+              a0 = lds_read_tr8(ab + (abase ^ ((mt + 1) << 4)));
+              a1 = lds_read_tr8(ab + (abase ^ ((mt + 1) << 4)) + 4096);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
@@ -184,42 +257,50 @@ __global__ __launch_bounds__(512) void pw_tile_kernel(ConvParams p, PwtGeom g) {
             __builtin_amdgcn_sched_barrier(0);
           }
         }
+        load_w(q + 2, wb[h]);
+        ++q;
       }
     }
 
     // ---- epilogue: lane (n, gi) holds frames 16 mt + 4 gi + (0..3) of channel co_w + 16 nt + n
-    if (g.dbg & 4) continue;
+    if (!active || (g.dbg & 4)) continue;
     bool fast = true;
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) fast = fast && sc[nt] >= 33;
-    const bool all_fast = __all(fast);                  // wave-uniform: one code path
-    if (p.res) {                                        // vmcnt(0): the residual tile is in LDS
-      __builtin_amdgcn_s_waitcnt(0x0f70);
-      asm volatile("" ::: "memory");
+    for (int nt = 0; nt < NT; ++nt) {
+      mc[nt] = stash[(2 * nt) * 64 + lane];
+      sc[nt] = stash[(2 * nt + 1) * 64 + lane];
+      fast = fast && sc[nt] >= 33;
     }
-    auto epilogue = [&](auto fast_tag, auto res_tag) {
-      constexpr bool FAST = decltype(fast_tag)::value, RES = decltype(res_tag)::value;
+    const bool all_fast = __all(fast);                  // wave-uniform: one code path
+    // Two variants only (all s >= 33, or the 64-bit form); the residual bytes are always added
+    // (zeros when there is no residual): more variants would share sub-expressions, which the
+    // compiler then hoists above the selecting branch for all accumulators at once.
+    const bool has_res = p.res != nullptr;
+    auto epilogue = [&](auto fast_tag) {
+      constexpr bool FAST = decltype(fast_tag)::value;
       const int32_t hi127 = 127;
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const int sh = FAST ? sc[nt] - 32 : sc[nt], rnd = FAST ? 1 << (sc[nt] - 33) : 0;
         uint32_t rw[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          rw[mt] = RES ? *reinterpret_cast<const uint32_t*>(stage + nt * 2048 + soff[mt]) : 0u;
+        for (int mt = 0; mt < MT; ++mt) rw[mt] = 0u;
+        if (has_res) {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+            rw[mt] = *reinterpret_cast<const uint32_t*>(stage + nt * 2048 + (sbase ^ (mt << 4)));
+        }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
           const int32_t a4[4] = {acc[mt][nt][0], acc[mt][nt][1], acc[mt][nt][2], acc[mt][nt][3]};
-          *reinterpret_cast<uint32_t*>(stage + nt * 2048 + soff[mt]) =
-              requant_pack4<FAST, RES>(a4, mc[nt], sh, rnd, rw[mt], lo, hi127);
+          *reinterpret_cast<uint32_t*>(stage + nt * 2048 + (sbase ^ (mt << 4))) =
+              requant_pack4<FAST, true>(a4, mc[nt], sh, rnd, rw[mt], lo, hi127);
+          if (mt & 1) __builtin_amdgcn_sched_barrier(0);   // bounds the live temporaries
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
     };
-    if (all_fast) {
-      if (p.res) epilogue(std::true_type{}, std::true_type{}); else epilogue(std::true_type{}, std::false_type{});
-    } else {
-      if (p.res) epilogue(std::false_type{}, std::true_type{}); else epilogue(std::false_type{}, std::false_type{});
-    }
+    if (all_fast) epilogue(std::true_type{}); else epilogue(std::false_type{});
     // rows out: lane -> (row 8 it + lane/8, slot lane%8) = unit u_l of channel co_w + row
 #pragma unroll
     for (int it = 0; it < 2 * NT; ++it) {
@@ -228,11 +309,13 @@ __global__ __launch_bounds__(512) void pw_tile_kernel(ConvParams p, PwtGeom g) {
       if (u_ok && co < p.Cout) *reinterpret_cast<v4i*>(p.y + yoff_l + (int64_t)co * p.Tout) = o;
     }
   }
+  wait_vm<0>();   // the clamped tail of the weight stream is still in flight: let it land
 }
 
 struct Choice { int MT, NT; };
 
-size_t lds_bytes(const ConvParams& p, int NT) { return (size_t)p.Cin * 128 + (size_t)8 * 16 * NT * 128; }
+// activation tile + per-wave staging + per-wave park space for m and s
+size_t lds_bytes(const ConvParams& p, int NT) { return (size_t)p.Cin * 128 + (size_t)8 * 16 * NT * 128 + (size_t)8 * 2 * NT * 64 * 4; }
 
 int num_cus() {
   static int n = 0;
@@ -288,15 +371,16 @@ hipError_t launch_t(const ConvParams& p, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int tiles = (g.G + MT - 1) / MT;
-  return launch_kernel(pw_tile_kernel<MT, NT>, dim3((unsigned)tiles), dim3(512), shmem, st, p, g);
+  g.tiles = (g.G + MT - 1) / MT;
+  g.tiles_per_xcd = (g.tiles + 7) / 8;
+  return launch_kernel(pw_tile_kernel<MT, NT>, dim3((unsigned)(8 * g.tiles_per_xcd)), dim3(512), shmem, st, p, g);
 }
 
 }  // namespace
 
 bool pw_tile_supported(const ConvParams& p) {
   if (p.depthwise || p.k != 1 || p.stride != 1 || p.pl != 0 || p.Tout != p.Tin) return false;
-  if (!p.w_packed || p.Cin % 64 != 0 || p.Cin > 1024 || p.Tin % 16 != 0) return false;
+  if (!p.w_packed || p.Cin % 128 != 0 || p.Cin > 1024 || p.Tin % 16 != 0) return false;
   if (p.xbs % 16 != 0 || p.ybs % 16 != 0) return false;
   if ((uintptr_t)p.x % 16 || (uintptr_t)p.y % 16 || (uintptr_t)p.w % 16 || (p.res && (uintptr_t)p.res % 16))
     return false;
