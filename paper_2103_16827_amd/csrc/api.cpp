@@ -68,10 +68,13 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
   return p;
 }
 
-enum class Kernel { Generic, DwMfma, GemmMfma, PwMfma, PwTile };
+enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwMfma, PwTile };
 
 Kernel pick_kernel(const ConvParams& p) {
-  if (p.depthwise) return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
+  if (p.depthwise) {
+    if (qasr::dw_pipe_supported(p)) return Kernel::DwPipe;
+    return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
+  }
   if (qasr::pw_tile_supported(p)) return Kernel::PwTile;
   if (qasr::pw_mfma_supported(p)) return Kernel::PwMfma;
   if (qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
@@ -81,6 +84,7 @@ Kernel pick_kernel(const ConvParams& p) {
 const char* kernel_name(Kernel k) {
   switch (k) {
     case Kernel::DwMfma: return "dw_mfma";
+    case Kernel::DwPipe: return "dw_pipe";
     case Kernel::GemmMfma: return "gemm_mfma";
     case Kernel::PwMfma: return "pw_mfma";
     case Kernel::PwTile: return "pw_tile";
@@ -92,6 +96,7 @@ qasr_status launch(const ConvParams& p, hipStream_t st) {
   hipError_t e;
   switch (pick_kernel(p)) {
     case Kernel::DwMfma: e = qasr::launch_dw_mfma(p, st); break;
+    case Kernel::DwPipe: e = qasr::launch_dw_pipe(p, st); break;
     case Kernel::GemmMfma: e = qasr::launch_gemm_mfma(p, st); break;
     case Kernel::PwMfma: e = qasr::launch_pw_mfma(p, st); break;
     case Kernel::PwTile: e = qasr::launch_pw_tile(p, st); break;

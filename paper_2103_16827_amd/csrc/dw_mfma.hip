@@ -38,6 +38,7 @@ struct DwGeom {
   int NCH;       // 16-byte chunks per strip buffer: groups + 4*KC - 1
   int nstrips;   // B * nseg
   int aligned_out;
+  int c_per_xcd; // channels per XCD: ceil(C / 8)
 };
 
 template <int KC, bool ALIGNED>
@@ -47,7 +48,10 @@ __global__ __launch_bounds__(256) void dw_mfma_kernel(ConvParams p, DwGeom g) {
   __shared__ unsigned char wrow[64 * KC + 16];                     // dilated, shifted weight row
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int c = blockIdx.x;
+  // Consecutive workgroups go round-robin to the 8 XCDs (one L2 each); rows of neighbouring
+  // channels share a cache line where they meet, so each XCD takes a contiguous range of channels.
+  const int c = (int)(blockIdx.x & 7) * g.c_per_xcd + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= g.c_per_xcd || c >= p.Cout) return;   // whole workgroup
   const int n = lane & 15, gi = lane >> 4;
   const int strip0 = (blockIdx.y * 4 + wave) * g.R;
   const int Rv = min(g.R, g.nstrips - strip0);                     // <= 0: this wave has no work
@@ -230,6 +234,7 @@ bool geometry(const ConvParams& p, DwGeom& g, int& KC) {
   }
   const int64_t gy = (nstrips + 4 * g.R - 1) / (4 * g.R);
   if (gy > 65535) return false;
+  g.c_per_xcd = (p.Cout + 7) / 8;
   g.aligned_out = (p.Tout % 4 == 0) && ((uintptr_t)p.y % 4 == 0) && (p.ybs % 4 == 0) &&
                   (!p.res || (uintptr_t)p.res % 4 == 0);
   return true;
@@ -237,7 +242,7 @@ bool geometry(const ConvParams& p, DwGeom& g, int& KC) {
 
 template <int KC>
 hipError_t launch_kc(const ConvParams& p, const DwGeom& g, hipStream_t st) {
-  const dim3 grid(p.Cout, (g.nstrips + 4 * g.R - 1) / (4 * g.R));
+  const dim3 grid(8 * g.c_per_xcd, (g.nstrips + 4 * g.R - 1) / (4 * g.R));
   const size_t shmem = (size_t)4 * g.R * g.NCH * 16;
   const bool aligned = (p.Tin % 16 == 0) && ((uintptr_t)p.x % 16 == 0) && (p.xbs % 16 == 0);
   if (aligned) return launch_kernel(dw_mfma_kernel<KC, true>, grid, dim3(256), shmem, st, p, g);

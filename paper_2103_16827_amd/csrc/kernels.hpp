@@ -29,6 +29,11 @@ hipError_t launch_gemm_mfma(const ConvParams& p, hipStream_t st);
 bool pw_mfma_supported(const ConvParams& p);
 hipError_t launch_pw_mfma(const ConvParams& p, hipStream_t st);
 
+// Depthwise convolution, same arithmetic, software-pipelined over the batch (reads and writes of
+// HBM overlap); needs aligned rows, no residual and enough rows per wave to pipeline.
+bool dw_pipe_supported(const ConvParams& p);
+hipError_t launch_dw_pipe(const ConvParams& p, hipStream_t st);
+
 // Pointwise convolution (k = 1), activation tile stationary in LDS (direct global->LDS loads);
 // needs packed weights, rows that are a multiple of 16 frames and Cin <= 1024.
 bool pw_tile_supported(const ConvParams& p);

@@ -1,0 +1,72 @@
+// Vector-memory requests whose completion the kernel tracks by hand (gfx950 only).
+//
+// The compiler's own wait insertion is exact only for requests it can see and, for direct
+// global->LDS loads, falls back to waiting for everything.  Kernels that keep several requests
+// in flight across loop iterations therefore issue them through inline assembly and wait with
+// explicit counts.  Requests of a wave complete in the order they were issued, so "at most N
+// outstanding" (s_waitcnt vmcnt(N)) means that all but the N youngest have completed; a wait with
+// too small an N only waits longer, one with too large an N reads data that has not arrived.
+// Every use of a register loaded this way must come after a tie() that follows the wait: the
+// empty volatile asm makes the value depend on that point of the instruction stream.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qasr {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+// 64 lanes x 16 bytes from per-lane global addresses to LDS at lds_wave_base + 16 * lane
+// (lds_wave_base must be wave-uniform).  Completion is counted by vmcnt.
+__device__ __forceinline__ void direct_load16(const void* gptr, const unsigned char* lds_wave_base) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(gptr), "s"(m0v) : "memory");
+}
+
+// Global loads whose completion the kernel waits for by hand (wait_vm / tie below).  The
+// compiler does not know that the result is still in flight, so every use has to come after a
+// tie() that follows the wait.
+__device__ __forceinline__ v4i gload16(const void* p) {
+  v4i r;
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  return r;
+}
+// same, through a raw buffer resource: address = base + voff (per lane) + soff (wave-uniform)
+__device__ __forceinline__ v4i bload16(v4i rsrc, uint32_t voff, uint32_t soff) {
+  v4i r;
+  asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(r) : "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+  return r;
+}
+__device__ __forceinline__ v4i make_rsrc(const void* base, uint32_t bytes) {
+  const uint64_t a = (uint64_t)(uintptr_t)base;
+  return (v4i){(int)(uint32_t)a, (int)(uint32_t)((a >> 32) & 0xffffu), (int)bytes, 0x00027000};
+}
+__device__ __forceinline__ int32_t gload4(const void* p) {
+  int32_t r;
+  asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  return r;
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+// at most n vector-memory operations outstanding (n wave-uniform); anything above 32 waits for all
+__device__ __forceinline__ void wait_vm_dyn(int n) {
+  switch (n) {
+#define QASR_W(N) case N: wait_vm<N>(); break;
+    QASR_W(1) QASR_W(2) QASR_W(3) QASR_W(4) QASR_W(5) QASR_W(6) QASR_W(7) QASR_W(8)
+    QASR_W(9) QASR_W(10) QASR_W(11) QASR_W(12) QASR_W(13) QASR_W(14) QASR_W(15) QASR_W(16)
+    QASR_W(17) QASR_W(18) QASR_W(19) QASR_W(20) QASR_W(21) QASR_W(22) QASR_W(23) QASR_W(24)
+    QASR_W(25) QASR_W(26) QASR_W(27) QASR_W(28) QASR_W(29) QASR_W(30) QASR_W(31) QASR_W(32)
+#undef QASR_W
+    default: wait_vm<0>(); break;
+  }
+}
+// makes every later use of v depend on this point of the (volatile-ordered) instruction stream
+__device__ __forceinline__ void tie(v4i& v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void tie(int32_t& v) { asm volatile("" : "+v"(v)); }
+
+}  // namespace qasr

@@ -171,7 +171,8 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
             flags = 0 if o.depthwise else Q.FLAG_W_PACKED
             name = Q.conv1d_kernel_name(desc_of(o, net.B, flags))
             if o.depthwise:
-                want = "dw_mfma"
+                # the pipelined kernel needs at least 3 rows per wave (4 waves per channel)
+                want = "dw_pipe" if net.B >= 12 else "dw_mfma"
             elif o.k == 1 and o.Tin % 16 == 0 and o.Cin <= 1024:
                 want = "pw_tile"
             elif o.k == 1 and o.Tin % 16 == 0 and o.Cin % 256 == 0:
