@@ -68,13 +68,14 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
   return p;
 }
 
-enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwMfma, PwTile };
+enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwMfma, PwTile, PwStream };
 
 Kernel pick_kernel(const ConvParams& p) {
   if (p.depthwise) {
     if (qasr::dw_pipe_supported(p)) return Kernel::DwPipe;
     return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
   }
+  if (qasr::pw_stream_supported(p)) return Kernel::PwStream;
   if (qasr::pw_tile_supported(p)) return Kernel::PwTile;
   if (qasr::pw_mfma_supported(p)) return Kernel::PwMfma;
   if (qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
@@ -88,6 +89,7 @@ const char* kernel_name(Kernel k) {
     case Kernel::GemmMfma: return "gemm_mfma";
     case Kernel::PwMfma: return "pw_mfma";
     case Kernel::PwTile: return "pw_tile";
+    case Kernel::PwStream: return "pw_stream";
     default: return "conv_generic";
   }
 }
@@ -100,6 +102,7 @@ qasr_status launch(const ConvParams& p, hipStream_t st) {
     case Kernel::GemmMfma: e = qasr::launch_gemm_mfma(p, st); break;
     case Kernel::PwMfma: e = qasr::launch_pw_mfma(p, st); break;
     case Kernel::PwTile: e = qasr::launch_pw_tile(p, st); break;
+    case Kernel::PwStream: e = qasr::launch_pw_stream(p, st); break;
     default: e = qasr::launch_conv_generic(p, st); break;
   }
   return hip_status(e);

@@ -39,4 +39,10 @@ hipError_t launch_dw_pipe(const ConvParams& p, hipStream_t st);
 bool pw_tile_supported(const ConvParams& p);
 hipError_t launch_pw_tile(const ConvParams& p, hipStream_t st);
 
+// Pointwise convolution (k = 1), weights stationary in registers, activations streamed through LDS
+// by persistent workgroups; needs packed weights, rows that are a multiple of 16 frames,
+// Cin in {256, 512, 2048} and at least 64 output channels per 16-channel tile column.
+bool pw_stream_supported(const ConvParams& p);
+hipError_t launch_pw_stream(const ConvParams& p, hipStream_t st);
+
 }  // namespace qasr

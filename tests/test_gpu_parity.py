@@ -173,10 +173,17 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
             if o.depthwise:
                 # the pipelined kernel needs at least 3 rows per wave (4 waves per channel)
                 want = "dw_pipe" if net.B >= 12 else "dw_mfma"
-            elif o.k == 1 and o.Tin % 16 == 0 and o.Cin <= 1024:
-                want = "pw_tile"
-            elif o.k == 1 and o.Tin % 16 == 0 and o.Cin % 256 == 0:
-                want = "pw_mfma"
+            elif o.k == 1 and o.Tin % 16 == 0:
+                # weights-in-registers kernel for the instantiated widths, else the tile kernels
+                nt = {4: 4 if o.Cout > 256 else 2, 8: 4}.get(o.Cin // 64 if o.Cin % 64 == 0 else 0)
+                if nt and o.Cout >= 64 * nt:
+                    want = "pw_stream"
+                elif o.Cin % 128 == 0 and o.Cin <= 1024:
+                    want = "pw_tile"
+                elif o.Cin % 256 == 0:
+                    want = "pw_mfma"
+                else:
+                    want = "gemm_mfma"
             else:
                 want = "gemm_mfma"
             assert name == want, (cfg, o.name, name)
