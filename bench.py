@@ -36,6 +36,22 @@ def op_algorithmic(op, B):
     return byts, op.macs(B)
 
 
+def measured_traffic(kernel, config):
+    """HBM bytes per launch of `kernel` on this configuration as the hardware counters saw them
+    (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy of known size): read from the committed
+    counter summary profiles/<kernel>_config<N>_hbm_traffic.txt, whose header gives the commands
+    that produced it; None when there is no such summary."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_config{config}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +61,9 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-passes", type=int, default=5, help="per-op timed passes for the roofline")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="after the steps, run one plain elementwise int8 kernel that reads and writes this many MiB "
+                         "(the known-size dispatch that calibrates the HBM byte counters of a --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch sharding across GPUs needs no kernel work "
@@ -89,6 +108,14 @@ def main():
     frames = net.B * net.Tin
     value = frames / (ms_per_step * 1e-3)
 
+    if args.calib_copy_mib > 0:
+        a = torch.zeros(args.calib_copy_mib << 20, dtype=torch.int8, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.bitwise_not(a, out=b)
+        torch.cuda.synchronize()
+        del a, b
+
     # ---- per-op device time (HIP events on the launch stream, inside the library)
     kernels = [enc.op_kernel(i) for i in range(enc.n_ops)]
     acc_ms = np.zeros(enc.n_ops)
@@ -104,7 +131,7 @@ def main():
     dom = max(fam, key=lambda k: fam[k]["ms"])
     d = fam[dom]
     avg_ms = d["ms"] / d["launches"]
-    if dom == "dw_mfma" or dom == "conv_generic":
+    if dom.startswith("dw_") or dom == "conv_generic":
         achieved = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS, "traffic": None}
@@ -112,6 +139,7 @@ def main():
         achieved = 2.0 * d["macs"] / d["launches"] / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                     "frac": achieved / INT8_PEAK_TOPS, "traffic": None}
+    roofline["traffic"] = measured_traffic(dom, args.config)
     roofline["avg_launch_us"] = avg_ms * 1e3
     roofline["launches_per_step"] = d["launches"]
     roofline["share_of_device_time"] = d["ms"] / float(op_ms.sum())

@@ -41,7 +41,6 @@ struct PwsGeom {
   int tiles;      // ceil(G / MT)
   int per_xcd;    // tiles per XCD: ceil(tiles / 8)
   int co16n;      // ceil(Cout / 16)
-  unsigned long long* stamps;   // tuning: per-wave clock stamps (5 per wave), or null
 };
 
 __device__ __forceinline__ v2i lds_read_tr8(const unsigned char* p) {
@@ -57,7 +56,6 @@ __global__ __launch_bounds__(512) void pw_stream_kernel(ConvParams p, PwsGeom g)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, gi = lane >> 4;
-  const unsigned long long ts0 = __builtin_amdgcn_s_memtime();
 
   // Workgroup -> tile: consecutive workgroups go round-robin to the 8 XCDs (one L2 each);
   // neighbouring tiles share cache lines at their common edge, so each XCD gets a contiguous run.
@@ -135,9 +133,7 @@ __global__ __launch_bounds__(512) void pw_stream_kernel(ConvParams p, PwsGeom g)
     tie(bv[nt]); tie(mc[nt]); tie(sc[nt]);
   }
   wait_vm<0>();
-  const unsigned long long ts1 = __builtin_amdgcn_s_memtime();
   __syncthreads();
-  const unsigned long long ts2 = __builtin_amdgcn_s_memtime();
   if (!active) return;
 
   bool fast = true;
@@ -227,13 +223,8 @@ __global__ __launch_bounds__(512) void pw_stream_kernel(ConvParams p, PwsGeom g)
   } else {
     if (has_res) run(std::false_type{}, std::true_type{}); else run(std::false_type{}, std::false_type{});
   }
-  const unsigned long long ts3 = __builtin_amdgcn_s_memtime();
   if (MT < 4) store_half(0);                   // (not reached inside the loop)
   if (MT > 4) store_half(1);
-  if (g.stamps && lane == 0) {
-    unsigned long long* d = g.stamps + ((size_t)tile * 8 + wave) * 5;
-    d[0] = ts0; d[1] = ts1; d[2] = ts2; d[3] = ts3; d[4] = __builtin_amdgcn_s_memtime();
-  }
 }
 
 struct Choice { int KCH, NT, splits; };
@@ -256,6 +247,7 @@ int num_cus() {
 
 // Shape-only part of the choice (no device query: usable without a GPU).
 bool pick(const ConvParams& p, Choice& c) {
+  if (getenv("QASR_NO_PW_STREAM")) return false;          // tuning: fall through to pw_tile
   if (p.depthwise || p.k != 1 || p.stride != 1 || p.pl != 0 || p.Tout != p.Tin) return false;
   if (!p.w_packed || p.Tin % 16 != 0 || p.Cin % 64 != 0) return false;
   if (p.xbs % 16 != 0 || p.ybs % 16 != 0) return false;
@@ -294,8 +286,6 @@ hipError_t launch_t(const ConvParams& p, const Choice& c, hipStream_t st) {
     const int v = atoi(e);
     if (v >= 1 && v <= 8) g.MT = v;
   }
-  g.stamps = nullptr;
-  if (const char* e = getenv("QASR_PWS_STAMPS")) g.stamps = (unsigned long long*)strtoull(e, nullptr, 0);
   g.tiles = (g.G + g.MT - 1) / g.MT;
   g.per_xcd = (g.tiles + 7) / 8;
   const size_t shmem = lds_bytes(KCH, NT);
