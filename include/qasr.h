@@ -147,8 +147,10 @@ qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t*
                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /* Same as qasr_encoder_forward, but brackets every op with HIP events, waits for completion and
- * writes each op's device time in milliseconds to op_ms[0..n_ops) (HOST memory).  For
- * profiling only: it synchronises and creates/destroys events. */
+ * writes each op's device time in milliseconds to op_ms[0..n_ops) (HOST memory): the interval
+ * between the events around the op minus the interval of two events recorded back to back with
+ * nothing between them (measured in the same call).  For profiling only: it synchronises and
+ * creates/destroys events. */
 qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, int8_t* y,
                                        void* workspace, size_t workspace_bytes, void* stream,
                                        float* op_ms);

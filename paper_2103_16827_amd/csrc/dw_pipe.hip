@@ -23,7 +23,8 @@
 // that every iteration issues the same number of requests.  Completion is waited for with explicit
 // counts (vmem.hpp): a wave's requests complete in order, loads and stores alike, so before
 // iteration i the wave allows exactly the requests issued after the loads of iteration i to stay
-// outstanding:  loads(i+1), loads(i+2) [L each] + stores(i-2), stores(i-1) [one per 256-frame tile].
+// outstanding:  loads(i+1), loads(i+2) [L each] + stores(i-2), stores(i-1) [one per 256-frame tile
+// of the iteration's whole pairs of tiles].
 // Needs 16-byte aligned rows that are a multiple of 16 frames and at most ~1000 frames long,
 // 4-byte aligned outputs and no residual operand; everything else is served by dw_mfma.hip.
 #include "kernels.hpp"
@@ -37,6 +38,9 @@ namespace qasr {
 
 namespace {
 
+// cache policy of the output stores (sc0 sc1): written through towards memory as they are issued,
+// so that little is left to write back when the kernel ends
+constexpr int kStoreThrough = 17;
 constexpr int kMaxTiles = 8; // 256-frame tiles per iteration: R * groups per strip <= 128
 
 struct DwpGeom {
@@ -54,8 +58,6 @@ template <int KC, int R, int NI>
 __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
   extern __shared__ __align__(16) unsigned char strips_lds[];      // [4 waves][3 buffers][R][NCH][16]
   __shared__ __align__(16) unsigned char a_lds[KC * 1024];         // A operand, register layout
-  __shared__ unsigned char wrow[64 * KC + 16];                     // dilated, shifted weight row
-  constexpr int L = R * NI;                                        // load requests per iteration
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -71,7 +73,7 @@ __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
   const int s_end = min(s_begin + g.spw, p.B);
   const int n_it = (s_end - s_begin + R - 1) / R;
 
-  // Requests of one iteration (always L of them): rows `row` .. `row + R - 1` into buffer `buf`.
+  // Requests of one iteration (always L of them, see below): rows `row` .. `row + R - 1` into buffer `buf`.
   // Chunk u of a row holds frames 16 (u - PH) .. +15; lanes whose chunk is padding stay out.
   const int8_t* const xc = p.x + (int64_t)c * p.Tin;
   const int rowbytes = g.NCH * 16;
@@ -83,6 +85,12 @@ __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
     lane_in[ni] = u < g.NCH && t >= 0 && t < p.Tin;
     lane_off[ni] = t;
   }
+  // A request in which no lane takes part is not issued at all (the compiler branches around it),
+  // so only the 64-chunk slices of a row that hold at least one chunk of data count.
+  int L = 0;
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+    if (__builtin_amdgcn_readfirstlane((int)(__ballot(lane_in[ni]) != 0))) L += R;
   auto issue = [&](int row, int buf) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -99,40 +107,68 @@ __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
     if (u < g.NCH && !lane_in[ni])
       for (int q = 0; q < 3 * R; ++q) *reinterpret_cast<v4i*>(my + q * rowbytes + u * 16) = (v4i){0, 0, 0, 0};
   }
+  // The channel's weights are requested before the rows: requests complete in order, so the
+  // Toeplitz operand can be built while the rows are still on their way.
+  // (So are the channel's constants: loads the compiler knew of would make it wait for every
+  // request of the wave, rows included, at their first use.)
+  int32_t bias = 0, mc = gload4(p.m + c), sc = gload4(p.s + c);
+  if (p.bias) bias = gload4(p.bias + c);
+  int32_t wj = 0;
+  if (tid < p.k) wj = gload_i8(p.w + (int64_t)c * p.k + tid);
+  int n_rows = 0;                               // row requests of this wave so far
+  // Only the first iteration's rows are requested now, the other two after the operand is built:
+  // all waves of the chip start together, and a request waits behind everything that entered
+  // the memory system before it, so what is needed first has to be asked for first chip-wide.
   if (s_begin < s_end) {          // (a wave without rows issues nothing and skips the loop below)
+    n_rows = L;
     issue(s_begin, 0);
+  }
+
+  // The 16-frame groups of an iteration's R rows form one flat list of columns; tile j takes
+  // columns 16 j .. 16 j + 15 (lane n -> column 16 j + n), so that the 256-frame tiles stay full
+  // across row ends.  The walk is the same in every iteration, so each lane keeps, per tile, the
+  // LDS offset of its operand and the offset of its 4 output frames from the iteration's first
+  // row.  Columns past the R rows and frames past the end of a row get an offset that the output
+  // resource rejects (a raw buffer store beyond num_records is dropped), as do rows past the
+  // wave's last: no lane masking.  Tiles are taken in pairs and every iteration issues exactly
+  // 2 * pairs stores (an odd last tile drags along a partner whose stores are all rejected).
+  int lds_off[kMaxTiles];
+  uint32_t out_off[kMaxTiles];
+#pragma unroll
+  for (int j = 0; j < kMaxTiles; ++j) {
+    int rr = 0, grp = 16 * j + n;               // column -> (row, group): at most R rows count
+#pragma unroll
+    for (int q = 0; q < R; ++q)
+      if (grp >= g.G) { grp -= g.G; ++rr; }
+    const bool in = rr < R && grp < g.G;
+    if (!in) { rr = R - 1; grp = 0; }           // reads stay inside the buffer, the store is rejected
+    const int t = 16 * grp + 4 * gi;
+    lds_off[j] = (rr * g.NCH + grp + gi) << 4;
+    out_off[j] = (in && t < p.Tout) ? (uint32_t)rr * (uint32_t)p.ybs + (uint32_t)t : 0xfffffff0u;
+  }
+
+  // ---- Toeplitz operand in the register layout of the matrix product: lane (m, gi) holds
+  // A[m, 64 kc + 16 gi + (0..15)].  Weight j sits at kappa = m + delta + j * dilation for every m:
+  // the thread that loaded it writes those 16 bytes into the zeroed image.
+#pragma unroll
+  for (int kc = 0; kc < KC; ++kc)
+    reinterpret_cast<uint32_t*>(a_lds)[kc * 256 + tid] = 0u;
+  __syncthreads();
+  wait_vm_dyn(n_rows);                          // everything requested before the rows is here
+  tie(wj); tie(bias); tie(mc); tie(sc);
+  if (tid < p.k) {
+    const int kap0 = g.delta + tid * p.dil;
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+      const int kap = kap0 + m;
+      a_lds[(kap >> 6) * 1024 + (((kap >> 4) & 3) * 16 + m) * 16 + (kap & 15)] = (unsigned char)wj;
+    }
+  }
+  __syncthreads();
+  if (s_begin < s_end) {
     issue(s_begin + R, 1);
     issue(s_begin + 2 * R, 2);
   }
-
-  // per-channel constants: uniform over the workgroup
-  const int32_t bias = p.bias ? p.bias[c] : 0;
-  const int32_t mc = p.m[c], sc = p.s[c];
-
-  // ---- Toeplitz operand: wrow[q] = w[j] where q - 15 - delta == j * dilation
-  for (int q = tid; q < 64 * KC + 16; q += 256) {
-    const int rel = q - 15 - g.delta;
-    int8_t v = 0;
-    if (rel >= 0) {
-      const int j = rel / p.dil;
-      if (j * p.dil == rel && j < p.k) v = p.w[(int64_t)c * p.k + j];
-    }
-    wrow[q] = (unsigned char)v;
-  }
-  __syncthreads();
-  {
-    // A[m, kappa] = wrow[kappa - m + 15]; lane (m, gi) holds kappa = 64 kc + 16 gi + (0..15).
-    const int al = tid >> 2, dwi = tid & 3;
-    const int am = al & 15, ag = al >> 4;
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-      const int base = 64 * kc + 16 * ag + 4 * dwi - am + 15;
-      const uint32_t v = (uint32_t)wrow[base] | ((uint32_t)wrow[base + 1] << 8) |
-                         ((uint32_t)wrow[base + 2] << 16) | ((uint32_t)wrow[base + 3] << 24);
-      reinterpret_cast<uint32_t*>(a_lds)[kc * 256 + tid] = v;
-    }
-  }
-  __syncthreads();
   v4i a[KC];
 #pragma unroll
   for (int kc = 0; kc < KC; ++kc) a[kc] = *reinterpret_cast<const v4i*>(a_lds + kc * 1024 + lane * 16);
@@ -142,73 +178,79 @@ __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
   const bool fast = sc >= 33;                           // uniform: one channel per workgroup
   const int sh = fast ? sc - 32 : sc, rnd = fast ? 1 << (sc - 33) : 0;
 
-  // The 16-frame groups of an iteration's R rows form one flat list of columns; tile j takes
-  // columns 16 j .. 16 j + 15 (lane n -> column 16 j + n), so that the 256-frame tiles stay full
-  // across row ends.  The walk is the same in every iteration, so each lane keeps, per tile, the
-  // LDS offset of its operand and the offset of its 4 output frames from the iteration's first
-  // row.  Columns past the R rows and frames past the end of a row get an offset that the output
-  // resource rejects (a raw buffer store beyond num_records is dropped), as do rows past the
-  // wave's last: no lane masking, and every iteration issues exactly g.tiles stores.
-  int lds_off[kMaxTiles];
-  uint32_t out_off[kMaxTiles];
-#pragma unroll
-  for (int j = 0; j < kMaxTiles; ++j) {
-    const int col = 16 * j + n;
-    const int rr = col / g.G, grp = col - rr * g.G;
-    const int t = 16 * grp + 4 * gi;
-    lds_off[j] = (min(rr, R - 1) * g.NCH + grp + gi) << 4;
-    out_off[j] = (rr < R && t < p.Tout) ? (uint32_t)rr * (uint32_t)p.ybs + (uint32_t)t : 0xfffffff0u;
-  }
-  const int tiles = g.tiles;
+  const int pairs = (g.tiles + 1) >> 1;
   int8_t* const yc = p.y + (int64_t)c * p.Tout;
 
-  auto iteration = [&](int it, int buf, auto fast_tag) {
+  // One iteration, software-pipelined over its NP tile pairs: the matrix products of pair q are
+  // issued, then the operands of pair q + 1 are read from LDS, then pair q - 1 is rescaled and
+  // stored, so that LDS and matrix-pipeline latencies pass under the vector arithmetic.
+  auto iteration = [&](int it, int buf, auto fast_tag, auto np_tag) __attribute__((always_inline)) {
     constexpr bool FAST = decltype(fast_tag)::value;
+    constexpr int NP = decltype(np_tag)::value;
     const int row = s_begin + it * R;
     const unsigned char* const rows_lds = my + buf * R * rowbytes;
-    wait_vm_dyn(2 * L + min(it, 2) * tiles);       // the rows of this iteration are in LDS
+    wait_vm_dyn(2 * L + min(it, 2) * 2 * NP);      // the rows of this iteration are in LDS
     asm volatile("" ::: "memory");
     if (g.dbg & 1) { issue(row + 3 * R, buf); return; }
 
-    // ---- tiles, two per step so that the LDS reads, matrix products and rescales of independent
-    // tiles overlap (an odd last tile drags along a partner whose stores are all rejected)
     const int Rv = min(R, s_end - row);
     const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
         yc + (int64_t)row * p.ybs, 0, (int)((uint32_t)(Rv - 1) * (uint32_t)p.ybs + (uint32_t)p.Tout), 0x00027000);
+    const v4i bias4 = {bias, bias, bias, bias};
+    v4i xb[2][2][KC];                              // [pair parity][tile of the pair][chunk]
+    v4i acc[2][2];
+    auto read_pair = [&](int q) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < kMaxTiles; j += 2) {
-      if (j < tiles) {
-        v4i acc[2];
+      for (int e = 0; e < 2; ++e)
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const unsigned char* bp = rows_lds + lds_off[j + e];
-          acc[e] = (v4i){bias, bias, bias, bias};
+        for (int kc = 0; kc < KC; ++kc)
+          xb[q & 1][e][kc] = *reinterpret_cast<const v4i*>(rows_lds + lds_off[2 * q + e] + kc * 64);
+    };
+    auto multiply_pair = [&](int q) __attribute__((always_inline)) {
 #pragma unroll
-          for (int kc = 0; kc < KC; ++kc) {
-            const v4i xb = *reinterpret_cast<const v4i*>(bp + kc * 64);
-            acc[e] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[kc], xb, acc[e], 0, 0, 0);
-          }
-        }
+      for (int kc = 0; kc < KC; ++kc)
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const int32_t a4[4] = {acc[e][0], acc[e][1], acc[e][2], acc[e][3]};
-          const uint32_t pk = requant_pack4<FAST, false>(a4, mc, sh, rnd, 0u, lo, hi127);
-          if (e == 0 || j + 1 < tiles)
-            __builtin_amdgcn_raw_buffer_store_b32(pk, yrs, out_off[j + e], 0, 0);
-        }
+        for (int e = 0; e < 2; ++e)
+          acc[q & 1][e] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[kc], xb[q & 1][e][kc], kc == 0 ? bias4 : acc[q & 1][e], 0, 0, 0);
+    };
+    auto finish_pair = [&](int q) __attribute__((always_inline)) {
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const v4i av = acc[q & 1][e];
+        const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
+        const uint32_t pk = requant_pack4<FAST, false>(a4, mc, sh, rnd, 0u, lo, hi127);
+        __builtin_amdgcn_raw_buffer_store_b32(pk, yrs, out_off[2 * q + e], 0, kStoreThrough);
       }
+    };
+    read_pair(0);
+#pragma unroll
+    for (int q = 0; q < NP; ++q) {
+      multiply_pair(q);
+      if (q + 1 < NP) read_pair(q + 1);
+      if (q > 0) finish_pair(q - 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    finish_pair(NP - 1);
     asm volatile("" ::: "memory");                 // every LDS read of this buffer has been consumed
     issue(row + 3 * R, buf);
   };
-
-  for (int it0 = 0; it0 < n_it; it0 += 3) {
+  auto run = [&](auto fast_tag, auto np_tag) __attribute__((always_inline)) {
+    for (int it0 = 0; it0 < n_it; it0 += 3) {
 #pragma unroll
-    for (int h = 0; h < 3; ++h) {
-      if (it0 + h >= n_it) break;
-      if (fast) iteration(it0 + h, h, std::true_type{});
-      else iteration(it0 + h, h, std::false_type{});
+      for (int h = 0; h < 3; ++h) {
+        if (it0 + h >= n_it) break;
+        iteration(it0 + h, h, fast_tag, np_tag);
+      }
     }
+  };
+  auto run_np = [&](auto np_tag) __attribute__((always_inline)) {
+    if (fast) run(std::true_type{}, np_tag); else run(std::false_type{}, np_tag);
+  };
+  switch (pairs) {
+    case 1: run_np(std::integral_constant<int, 1>{}); break;
+    case 2: run_np(std::integral_constant<int, 2>{}); break;
+    case 3: run_np(std::integral_constant<int, 3>{}); break;
+    default: run_np(std::integral_constant<int, 4>{}); break;
   }
   wait_vm<0>();   // the look-ahead requests past the last iteration are still in flight
 }
@@ -233,13 +275,15 @@ bool plan(const ConvParams& p, DwpGeom& g, Plan& pl) {
   g.dbg = 0;
   if (const char* e = getenv("QASR_DWP_DBG")) g.dbg = atoi(e);
 
-  // Batch splits S (workgroups per channel) and rows per iteration R: aim at >= 512 workgroups
-  // with at least 3 iterations per wave; R = 2 keeps the 256-frame tiles fuller across row ends.
+  // Batch splits S (workgroups per channel) and rows per iteration R.  Measured on the 512- and
+  // 256-channel layers at batch 32: about 1024 workgroups (4 waves per SIMD) with one row per
+  // iteration beat fewer, longer-running waves; two rows per iteration (fuller 256-frame tiles
+  // across row ends) only pay once a wave has many iterations.
   const int64_t rows = p.B;
   pl.R = 1;
   pl.S = 1;
-  if (pl.NI == 1 && 2 * g.G <= 16 * kMaxTiles && (int64_t)p.Cout >= 512 && rows / (4 * 2) >= 3) pl.R = 2;
-  while ((int64_t)p.Cout * pl.S < 512 && rows / ((int64_t)4 * pl.R * (pl.S * 2)) >= 3) pl.S *= 2;
+  while ((int64_t)p.Cout * pl.S < 1024 && rows / ((int64_t)4 * (pl.S * 2)) >= 3) pl.S *= 2;
+  if (pl.NI == 1 && 2 * g.G <= 16 * kMaxTiles && rows / ((int64_t)4 * pl.S) >= 12) pl.R = 2;
   if (const char* e = getenv("QASR_DWP")) {              // tuning override: "R,S"
     int r = 0, s = 0;
     if (sscanf(e, "%d,%d", &r, &s) == 2 && (r == 1 || (r == 2 && pl.NI == 1 && 2 * g.G <= 16 * kMaxTiles)) &&
@@ -249,7 +293,7 @@ bool plan(const ConvParams& p, DwpGeom& g, Plan& pl) {
   }
   if (pl.R * g.G > 16 * kMaxTiles) return false;
   g.tiles = (pl.R * g.G + 15) / 16;
-  if (2 * pl.R * pl.NI + 2 * g.tiles > 32) return false;   // the hand-counted waits go up to 32
+  if (2 * pl.R * pl.NI + 4 * ((g.tiles + 1) / 2) > 32) return false;   // the hand-counted waits go up to 32
   // rows per wave: the batch split over S workgroups x 4 waves, rounded up to a multiple of R
   int64_t spw = (rows + (int64_t)4 * pl.S - 1) / ((int64_t)4 * pl.S);
   spw = (spw + pl.R - 1) / pl.R * pl.R;

@@ -45,4 +45,10 @@ hipError_t launch_pw_tile(const ConvParams& p, hipStream_t st);
 bool pw_stream_supported(const ConvParams& p);
 hipError_t launch_pw_stream(const ConvParams& p, hipStream_t st);
 
+// Pointwise convolution (k = 1), activation tile stationary in LDS, output channels in passes of
+// 256 whose epilogues run in between the matrix products of the following pass; needs packed
+// weights, rows that are a multiple of 16 frames, Cin in {256, 512} and 256 <= Cout <= 2048.
+bool pw_pipe_supported(const ConvParams& p);
+hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st);
+
 }  // namespace qasr

@@ -1,0 +1,431 @@
+// Pointwise (k = 1) int8 convolution  Y[co, t] = sum_ci W[co, ci] * X[ci, t]  on the gfx950 int8
+// matrix cores, activation tile stationary in LDS, output channels in software-pipelined passes,
+// with the fused epilogue (bias, dyadic rescale, residual, clamp).
+//
+// Tile, LDS layout, transpose reads, weight stream and staging are those of pw_tile.hip: a
+// workgroup of 8 waves owns MT consecutive 16-frame groups and all input channels of them; wave w
+// computes output channels 32 * (8 * pass + w) .. + 32 in pass `pass`.  What is different is the
+// order of work inside a wave.  In pw_tile a wave multiplies, then rescales and stores, and since
+// the two waves that share a SIMD do the same, the matrix pipeline idles during every epilogue.
+// Here the epilogue of pass p - 1 (accumulator set (p - 1) mod 2) is issued in between the matrix
+// products of pass p: a wave issues in order, so vector instructions placed between two products
+// execute while the first one occupies the matrix pipeline.  Every chunk step of the multiply
+// loop (64 input channels: MT transpose-read pairs, 2 MT products) carries its share of the 2 MT
+// epilogue blocks of the pass before, cut into pieces of 3 to 4 vector instructions; scheduling
+// fences pin the pattern   product, piece | product, piece | ...
+// The rows of pass p - 1 leave at the end of pass p's loop and drain under pass p + 1.  Only the
+// last pass's epilogue is exposed.  A pass whose s values are not all >= 33 (64-bit rescale), or a
+// layer without relu, is not pipelined: its epilogue follows its own loop, as in pw_tile.
+//
+// Vector-memory completion is tracked by hand (vmem.hpp): the wave counts the requests it issues
+// (`seq`) and remembers the count after each request it will wait for, so "everything up to that
+// request has completed" is  vmcnt(seq - mark).  Nothing that is in flight lives in a compiler
+// variable across the pass loop except the two weight buffers, whose every use follows a tie().
+#include "kernels.hpp"
+#include "vmem.hpp"
+
+#include <cstdlib>
+#include <type_traits>
+
+namespace qasr {
+
+namespace {
+
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+
+// cache policy of the output stores (sc0 sc1): written through towards memory as they are issued,
+// so that little is left to write back when the kernel ends
+constexpr int kStoreThrough = 17;
+constexpr int NT = 2;           // 16-channel columns per wave and pass
+constexpr int ROWS = 16 * NT;   // output channels of a wave and pass
+constexpr int MAXP = 8;         // passes (Cout <= 2048): bounds the constants parked in LDS
+
+struct PwpGeom {
+  int G;        // 16-frame groups in total: B * Tin / 16
+  int gpr;      // groups per row: Tin / 16
+  int passes;   // ceil(Cout / 256)
+  int co16n;    // ceil(Cout / 16)
+  int tiles, tiles_per_xcd;
+};
+
+__device__ __forceinline__ v2i lds_read_tr8(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+      (v2i __attribute__((address_space(3)))*)(const_cast<unsigned char*>(p)));
+}
+
+// One dword per active lane from per-lane global addresses to LDS at lds_wave_base + 4 * lane.
+__device__ __forceinline__ void direct_load4(const void* gptr, const unsigned char* lds_wave_base) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :: "v"(gptr), "s"(m0v) : "memory");
+}
+
+// LDS: [KCH * 64 rows][128 B]  activation tile (unit u of row r in slot u ^ (r & 7))
+//      [8 waves][2][ROWS][128 B] staging: residual rows in, int8 rows out, per wave and pass parity
+//      [8 waves][MAXP][NT][3][16] dwords: bias, m, s of the wave's channels of every pass
+template <int KCH>
+constexpr int lds_bytes_c() { return KCH * 8192 + 8 * 2 * ROWS * 128 + 8 * MAXP * NT * 3 * 64; }
+
+template <int MT, int KCH>
+__global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
+  extern __shared__ __align__(128) unsigned char xs[];
+  constexpr int NB = MT * NT;                     // epilogue blocks of a pass
+  static_assert(KCH == 4 || KCH == 8, "pieces per product");
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n = lane & 15, gi = lane >> 4;
+  // Workgroup -> tile: consecutive workgroups go round-robin to the 8 XCDs (one L2 each);
+  // neighbouring tiles share the cache lines at their common edge, so each XCD gets a contiguous run.
+  const int tile = (int)(blockIdx.x & 7) * g.tiles_per_xcd + (int)(blockIdx.x >> 3);
+  if ((blockIdx.x >> 3) >= (unsigned)g.tiles_per_xcd || tile >= g.tiles) return;   // whole workgroup
+  const int g0 = tile * MT;
+  // passes in which this wave has channels (>= 1: Cout >= 256); it leaves after them
+  const int P = min(g.passes, (p.Cout - wave * ROWS + 8 * ROWS - 1) / (8 * ROWS));
+
+  // lane -> (row lane/8 of a block of 8 rows, slot lane%8); the unit in that slot, slot ^ (row & 7),
+  // is the same for every block of 8 rows: one lane -> unit map for activation loads, residual
+  // loads and output stores.
+  const int u_l = (lane & 7) ^ (lane >> 3);
+  const int gq_l = g0 + u_l;
+  const bool u_ok = u_l < MT && gq_l < g.G;
+  const int b_l = gq_l / g.gpr, t16_l = gq_l - b_l * g.gpr;
+  const int64_t yoff_l = (int64_t)b_l * p.ybs + 16 * t16_l;       // of this lane's unit
+  unsigned char* const stage0 = xs + KCH * 8192 + wave * (2 * ROWS * 128);
+  unsigned char* const cst0 = xs + KCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
+  const bool has_res = p.res != nullptr;
+  const uint32_t resmask = has_res ? 0xffffffffu : 0u;
+
+  int seq = 0;                                   // vector-memory requests issued by this wave
+  int mark_r[2] = {0, 0}, mark_c = 0, mark_w[2] = {0, 0}, mark_x[3] = {0, 0, 0};
+
+  auto issue_residual = [&](int ps, int par) __attribute__((always_inline)) {   // residual rows of pass ps -> stage[par]
+    if (has_res) {
+      const int co_w = (ps * 8 + wave) * ROWS;
+#pragma unroll
+      for (int it = 0; it < 2 * NT; ++it) {
+        const int co = co_w + 8 * it + (lane >> 3);
+        if (u_ok && co < p.Cout)
+          direct_load16(p.res + yoff_l + (int64_t)co * p.Tout, stage0 + par * (ROWS * 128) + it * 1024);
+        if (co_w + 8 * it < p.Cout) ++seq;       // issued iff some lane had a row (lane 0 has unit 0)
+      }
+    }
+    mark_r[par] = seq;
+  };
+  // weight stream: chunk q of the flat (pass, chunk) sequence, clamped at its end
+  const int Q = P * KCH;
+  const v4i wrsrc = make_rsrc(p.w, (uint32_t)g.co16n * (uint32_t)KCH * 1024u);
+  const uint32_t wlane = (uint32_t)lane * 16;
+  v4i wb[2][NT];
+  auto issue_w = [&](int q, int h) __attribute__((always_inline)) {
+    q = q < Q - 1 ? q : Q - 1;
+    const int ps = q / KCH, kc = q - ps * KCH;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int co16 = min((ps * 8 + wave) * NT + nt, g.co16n - 1);
+      wb[h][nt] = bload16(wrsrc, wlane, (uint32_t)(co16 * KCH + kc) * 1024u);
+    }
+    seq += NT;
+    mark_w[h] = seq;
+  };
+
+  // ---- requests of the start: residual of pass 0, constants of all passes, then weights of
+  // chunks 0 and 1 in between the activation chunks (the first products need only 64 channels)
+  issue_residual(0, 0);
+  for (int ps = 0; ps < P; ++ps) {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      const int co = min((ps * 8 + wave) * ROWS + 16 * nt + n, p.Cout - 1);
+      unsigned char* d = cst0 + (ps * NT + nt) * (3 * 64);
+      if (lane < 16) {
+        if (p.bias) direct_load4(p.bias + co, d);
+        direct_load4(p.m + co, d + 64);
+        direct_load4(p.s + co, d + 128);
+      }
+      seq += p.bias ? 3 : 2;
+    }
+  }
+  mark_c = seq;
+  {
+    const int r = 8 * wave + (lane >> 3);
+    const int8_t* src = p.x + (int64_t)b_l * p.xbs + (int64_t)r * p.Tin + 16 * t16_l;
+    const int64_t step = (int64_t)64 * p.Tin;
+    unsigned char* dst = xs + 8 * wave * 128;
+    issue_w(0, 0);
+    if (u_ok) direct_load16(src, dst);
+    mark_x[0] = ++seq;
+    issue_w(1, 1);
+#pragma unroll
+    for (int kc = 1; kc < KCH; ++kc) {
+      if (u_ok) direct_load16(src + kc * step, dst + kc * 8192);
+      ++seq;
+      if (kc == 1) mark_x[1] = seq;
+    }
+    mark_x[2] = seq;                              // all of the tile
+  }
+
+  // per-lane constants of the transpose reads, staging accesses and row stores (see pw_tile.hip)
+  const int l16 = lane & 15, j = l16 >> 1;
+  const uint32_t abase = (uint32_t)((8 * gi + j) * 128 + 8 * (l16 & 1)) | (uint32_t)(j << 4);
+  const uint32_t sbase = (uint32_t)(n * 128 + 4 * gi) | (uint32_t)((n & 7) << 4);   // stage row 16 nt + n
+  const int lo = p.relu ? 0 : -128;
+  const int32_t hi127 = 127;
+  const uint32_t y_lane = u_ok ? (uint32_t)yoff_l + (uint32_t)(lane >> 3) * (uint32_t)p.Tout : 0xfffffff0u;
+
+  v4i acc[2][MT][NT];
+  int32_t mc[NT], sh[NT], rnd[NT];                // rescale constants of the pass whose epilogue is pending
+
+  // one epilogue block: lane (n, gi) holds frames 16 mt + 4 gi + (0..3) of channel 16 nt + n
+  auto block = [&](int par, int e, auto fast_tag) __attribute__((always_inline)) {
+    constexpr bool FAST = decltype(fast_tag)::value;
+    const int mt = e / NT, nt = e % NT;
+    uint32_t* const sp = reinterpret_cast<uint32_t*>(stage0 + par * (ROWS * 128) + nt * 2048 + (sbase ^ (uint32_t)(mt << 4)));
+    const uint32_t rw = *sp & resmask;
+    const v4i av = acc[par][mt][nt];
+    const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
+    *sp = requant_pack4<FAST, true>(a4, mc[nt], sh[nt], rnd[nt], rw, lo, hi127);
+  };
+  // The pipelined case (short-form rescale, relu): the block is cut into 8 pieces of 3 to 4 vector
+  // instructions, one piece per matrix product of the following pass (two when Cin = 256), so
+  // that the vector unit works in the shadow of the matrix pipeline.  Piece j of block e:
+  //   j = 0, 2, 4, 6: t[j/2] = (mulhi(acc[j/2], m) + rnd) >> sh
+  //   j = 1, 3, 5, 7: t[j/2] = clamp(t[j/2] + residual byte j/2, 0, 127), and the packing steps
+  // The residual word of block e + 1 is read during block e (rw_next).
+  uint32_t pt[4], p01 = 0, rw_cur = 0, rw_next = 0;
+  auto stage_word = [&](int par, int e) __attribute__((always_inline)) {
+    const int mt = e / NT, nt = e % NT;
+    return reinterpret_cast<uint32_t*>(stage0 + par * (ROWS * 128) + nt * 2048 + (sbase ^ (uint32_t)(mt << 4)));
+  };
+  auto piece = [&](int par, int pidx) __attribute__((always_inline)) {
+    const int e = pidx >> 3, j = pidx & 7, i = j >> 1;
+    const int mt = e / NT, nt = e % NT;
+    if (j == 0) rw_cur = rw_next & resmask;
+    if (j == 4 && e + 1 < NB) rw_next = *stage_word(par, e + 1);
+    if ((j & 1) == 0) {
+      pt[i] = (uint32_t)(((int32_t)__mulhi(acc[par][mt][nt][i], mc[nt]) + rnd[nt]) >> sh[nt]);
+    } else {
+      const int32_t t = (int32_t)pt[i] + (int32_t)(int8_t)(rw_cur >> (8 * i));
+      pt[i] = (uint32_t)min(max(t, 0), 127);
+      if (i == 1) p01 = pt[0] | (pt[1] << 8);
+      if (i == 3) *stage_word(par, e) = p01 | (pt[2] << 16) | (pt[3] << 24);
+    }
+  };
+  // rows of pass ps out of stage[par]: lane -> (row 8 it + lane/8, slot lane%8)
+  auto store_rows = [&](int ps, int par) __attribute__((always_inline)) {
+    const int co_w = (ps * 8 + wave) * ROWS;
+    const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
+        p.y + (int64_t)co_w * p.Tout, 0, 0x7ffffff0, 0x00027000);
+#pragma unroll
+    for (int it = 0; it < 2 * NT; ++it) {
+      const v4i o = *reinterpret_cast<const v4i*>(stage0 + par * (ROWS * 128) + it * 1024 + lane * 16);
+      const bool ok = u_ok && co_w + 8 * it + (lane >> 3) < p.Cout;
+      const v4u ov = {(unsigned)o.x, (unsigned)o.y, (unsigned)o.z, (unsigned)o.w};
+      const uint32_t off = ok ? y_lane + (uint32_t)(8 * it) * (uint32_t)p.Tout : 0xfffffff0u;
+      __builtin_amdgcn_raw_buffer_store_b128(ov, yrs, off, 0, kStoreThrough);
+    }
+  };
+  constexpr int STORE_REQS = 2 * NT;              // requests of one store_rows
+  // the epilogue of pass ps on its own
+  auto epilogue_alone = [&](int ps, int par, auto fast_tag) __attribute__((always_inline)) {
+    wait_vm_dyn(seq - mark_r[par]);
+#pragma unroll
+    for (int e = 0; e < NB; ++e) {
+      block(par, e, fast_tag);
+      if (e & 1) __builtin_amdgcn_sched_barrier(0);         // bounds the live temporaries
+    }
+    store_rows(ps, par);
+    seq += STORE_REQS;
+  };
+
+  bool pending = false;       // the pass before awaits its (short-form) epilogue
+  // The multiply loop of pass ps into accumulator set par; PREV: the epilogue of pass ps - 1 rides along.
+  // (FIRST: pass 0, which also waits for the activation chunks and synchronises the waves)
+  auto multiply = [&](int ps, int par, auto prev_tag, auto first_tag) __attribute__((always_inline)) {
+    constexpr bool PREV = decltype(prev_tag)::value, FIRST = decltype(first_tag)::value;
+    // bias of this pass out of LDS (constants of all passes were requested at the start)
+    if (FIRST) wait_vm_dyn(seq - mark_c);
+    if (!FIRST) issue_residual(ps, par);      // stage[par] is free: its rows left at the end of pass ps - 1
+    {
+      const unsigned char* c = cst0 + ps * (NT * 3 * 64) + 4 * n;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int32_t bv = p.bias ? *reinterpret_cast<const int32_t*>(c + nt * 192) : 0;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[par][mt][nt] = (v4i){bv, bv, bv, bv};
+      }
+    }
+    if (PREV) {
+      wait_vm_dyn(seq - mark_r[par ^ 1]);                   // residual rows of the pass before
+      rw_next = *stage_word(par ^ 1, 0);
+    }
+
+#pragma unroll
+    for (int kk = 0; kk < KCH; ++kk) {
+      const int h = kk & 1;                       // KCH is even: the buffer parity restarts per pass
+      // weights of this chunk and, in pass 0, the activation chunk(s) needed so far
+      if (FIRST) {
+        {
+          const int mw = mark_w[h], mx = mark_x[kk < 2 ? kk : 2];   // (by value: no references to the marks)
+          wait_vm_dyn(seq - (mw > mx ? mw : mx));
+        }
+      } else if (kk < 2) {
+        wait_vm_dyn(seq - mark_w[h]);
+      } else {
+        wait_vm<NT>();                            // only the next chunk's weights are younger
+      }
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) tie(wb[h][nt]);
+      if (FIRST && kk <= 2) __syncthreads();      // publishes the other waves' rows of the chunk(s)
+      {
+        const unsigned char* ab = xs + kk * 8192;
+        v2i a0 = lds_read_tr8(ab + abase);
+        v2i a1 = lds_read_tr8(ab + abase + 4096);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const v4i a = {a0.x, a0.y, a1.x, a1.y};
+          if (mt + 1 < MT) {
+            a0 = lds_read_tr8(ab + (abase ^ (uint32_t)((mt + 1) << 4)));
+            a1 = lds_read_tr8(ab + (abase ^ (uint32_t)((mt + 1) << 4)) + 4096);
+          }
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+            acc[par][mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, wb[h][nt], acc[par][mt][nt], 0, 0, 0);
+            if (PREV) {
+              constexpr int R = 8 / KCH;          // pieces per product: 8 NB pieces over KCH MT NT products
+              const int slot = (kk * MT + mt) * NT + nt;
+#pragma unroll
+              for (int r = 0; r < R; ++r) piece(par ^ 1, slot * R + r);
+              __builtin_amdgcn_sched_barrier(0);  // one product, its pieces, nothing else
+            }
+          }
+          if (!PREV) __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      issue_w(ps * KCH + kk + 2, h);
+    }
+    if (PREV) store_rows(ps - 1, par ^ 1);       // (the caller counts these requests)
+  };
+  // One pass: multiply, then either leave the epilogue pending for the next pass (short-form
+  // rescale and a next pass exists) or do it now.
+  auto do_pass = [&](int ps, int par, auto first_tag) __attribute__((always_inline)) {
+    if (decltype(first_tag)::value) multiply(ps, par, std::false_type{}, std::true_type{});
+    else if (pending) multiply(ps, par, std::true_type{}, std::false_type{});
+    else multiply(ps, par, std::false_type{}, std::false_type{});
+    seq += pending ? STORE_REQS : 0;      // rows of the pass before, stored at the end of the loop
+    // rescale constants of this pass
+    const unsigned char* c = cst0 + ps * (NT * 3 * 64) + 4 * n;
+    bool fast = true;
+    int32_t s_[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      mc[nt] = *reinterpret_cast<const int32_t*>(c + nt * 192 + 64);
+      s_[nt] = *reinterpret_cast<const int32_t*>(c + nt * 192 + 128);
+      fast = fast && s_[nt] >= 33;
+    }
+    const bool all_fast = __builtin_amdgcn_readfirstlane((int)__all(fast)) != 0;   // wave-uniform, and known to be
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      sh[nt] = all_fast ? s_[nt] - 32 : s_[nt];
+      rnd[nt] = all_fast ? 1 << ((s_[nt] - 33) & 31) : 0;
+    }
+    if (all_fast && p.relu && ps + 1 < P) {
+      pending = true;
+    } else {
+      pending = false;
+      if (all_fast) epilogue_alone(ps, par, std::true_type{}); else epilogue_alone(ps, par, std::false_type{});
+    }
+  };
+  do_pass(0, 0, std::true_type{});
+  for (int ps = 1; ps < P; ps += 2) {
+    do_pass(ps, 1, std::false_type{});
+    if (ps + 1 < P) do_pass(ps + 1, 0, std::false_type{});
+  }
+  wait_vm<0>();   // the clamped tail of the weight stream is still in flight: let it land
+}
+
+struct Choice { int MT, KCH; };
+
+size_t lds_bytes(int KCH) { return KCH == 4 ? lds_bytes_c<4>() : lds_bytes_c<8>(); }
+
+int num_cus() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+      n = v;
+    else
+      n = 256;
+  }
+  return n;
+}
+
+// Shape-only part of the choice (no device query: usable without a GPU).
+bool pick(const ConvParams& p, Choice& c, int cus) {
+  if (getenv("QASR_NO_PW_PIPE")) return false;            // tuning: fall through to the other kernels
+  if (p.depthwise || p.k != 1 || p.stride != 1 || p.pl != 0 || p.Tout != p.Tin) return false;
+  if (!p.w_packed || p.Tin % 16 != 0) return false;
+  if (p.Cin != 256 && p.Cin != 512) return false;         // instantiated widths
+  if (p.Cout < 8 * ROWS || p.Cout > MAXP * 8 * ROWS) return false;   // every wave has channels in pass 0
+  if (p.xbs % 16 != 0 || p.ybs % 16 != 0) return false;
+  if ((uintptr_t)p.x % 16 || (uintptr_t)p.y % 16 || (uintptr_t)p.w % 16 || (p.res && (uintptr_t)p.res % 16))
+    return false;
+  if ((int64_t)p.B * p.ybs >= 0x7ffffff0LL) return false;          // 32-bit output offsets
+  const int64_t G = (int64_t)p.B * (p.Tin / 16);
+  if (G > 0x3fffffff) return false;
+  c.KCH = p.Cin / 64;
+  // groups per tile: least makespan over the CUs (one workgroup per CU at a time), with a
+  // per-tile overhead worth about one group
+  double best = 1e300;
+  c.MT = 7;
+  for (int MT = 4; MT <= 8; ++MT) {
+    const int64_t tiles = (G + MT - 1) / MT;
+    const double cost = (double)((tiles + cus - 1) / cus) * (MT + 1.0);
+    if (cost < best - 1e-9) { best = cost; c.MT = MT; }
+  }
+  if (const char* e = getenv("QASR_PWP_MT")) {            // tuning override
+    const int mt = atoi(e);
+    if (mt >= 4 && mt <= 8) c.MT = mt;
+  }
+  return lds_bytes(c.KCH) <= 160 * 1024;
+}
+
+template <int MT, int KCH>
+hipError_t launch_t(const ConvParams& p, hipStream_t st) {
+  PwpGeom g;
+  g.gpr = p.Tin / 16;
+  g.G = p.B * g.gpr;
+  g.passes = (p.Cout + 8 * ROWS - 1) / (8 * ROWS);
+  g.co16n = (p.Cout + 15) / 16;
+  g.tiles = (g.G + MT - 1) / MT;
+  g.tiles_per_xcd = (g.tiles + 7) / 8;
+  static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute((const void*)pw_pipe_kernel<MT, KCH>,
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  return launch_kernel(pw_pipe_kernel<MT, KCH>, dim3((unsigned)(8 * g.tiles_per_xcd)), dim3(512),
+                       (size_t)lds_bytes_c<KCH>(), st, p, g);
+}
+
+}  // namespace
+
+bool pw_pipe_supported(const ConvParams& p) {
+  Choice c;
+  return pick(p, c, 256);
+}
+
+hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st) {
+  Choice c;
+  if (!pick(p, c, num_cus())) return hipErrorInvalidValue;
+#define QASR_CASE(M, K) if (c.MT == M && c.KCH == K) return launch_t<M, K>(p, st);
+  QASR_CASE(4, 4) QASR_CASE(5, 4) QASR_CASE(6, 4) QASR_CASE(7, 4) QASR_CASE(8, 4)
+  QASR_CASE(4, 8) QASR_CASE(5, 8) QASR_CASE(6, 8) QASR_CASE(7, 8) QASR_CASE(8, 8)
+#undef QASR_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace qasr

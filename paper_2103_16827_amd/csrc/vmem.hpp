@@ -49,6 +49,11 @@ __device__ __forceinline__ int32_t gload4(const void* p) {
   asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
   return r;
 }
+__device__ __forceinline__ int32_t gload_i8(const void* p) {   // one sign-extended byte
+  int32_t r;
+  asm volatile("global_load_sbyte %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  return r;
+}
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");

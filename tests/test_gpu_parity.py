@@ -163,6 +163,59 @@ def test_real_shape_layers(kw):
     run_layer_case(layer_case(**kw))
 
 
+# The pipelined depthwise kernel (batches of 12 and more): one and two 64-chunk slices per row,
+# short rows that share a 256-frame tile, long rows, every rescale form, odd batch sizes.
+DWPIPE = [
+    dict(name="dwp_k33", B=16, Cin=24, Cout=24, T=800, k=33, dw=True, bias=False),
+    dict(name="dwp_k87_d2_two_slices", B=12, Cin=16, Cout=16, T=800, k=87, dil=2, dw=True, bias=False),
+    dict(name="dwp_k75_bias", B=32, Cin=8, Cout=8, T=800, k=75, dw=True, relu=False),
+    dict(name="dwp_long_rows", B=13, Cin=8, Cout=8, T=1600, k=39, dw=True),
+    dict(name="dwp_short_rows", B=29, Cin=40, Cout=40, T=208, k=33, dw=True, relu=False),
+    dict(name="dwp_generic_s", B=12, Cin=16, Cout=16, T=320, k=33, dw=True, s_lo=20, s_hi=40),
+    dict(name="dwp_minus128_k32", B=14, Cin=16, Cout=16, T=400, k=32, dw=True, wmin=-128, bias=False),
+]
+
+
+@pytest.mark.parametrize("kw", DWPIPE, ids=[c["name"] for c in DWPIPE])
+def test_pipelined_depthwise_layers(kw):
+    assert run_layer_case(layer_case(**kw)) == "dw_pipe"
+
+
+@pytest.mark.parametrize("rs", ["2,1", "1,1", "1,2", "2,2"])
+def test_pipelined_depthwise_row_and_split_choices(rs, monkeypatch):
+    """Rows per iteration and batch splits other than the ones the heuristic picks."""
+    monkeypatch.setenv("QASR_DWP", rs)
+    assert run_layer_case(layer_case(name="dwp_rs", B=48, Cin=8, Cout=8, T=400, k=51, dw=True)) == "dw_pipe"
+
+
+# The pipelined pointwise kernel: 2..8 passes of 256 output channels, a last pass that only some
+# waves take part in, rows that leave a ragged last tile, every epilogue variant.
+PIPE = [
+    dict(name="pipe_512_1024_res", B=1, Cin=512, Cout=1024, T=800, res=True, packed=True),
+    dict(name="pipe_512_2048_norelu", B=1, Cin=512, Cout=2048, T=400, relu=False, packed=True),
+    dict(name="pipe_256_600_ragged", B=3, Cin=256, Cout=600, T=336, res=True, packed=True),
+    dict(name="pipe_512_264_nobias", B=2, Cin=512, Cout=264, T=176, bias=False, packed=True),
+    dict(name="pipe_512_512_generic_s", B=1, Cin=512, Cout=512, T=320, res=True, s_lo=20, s_hi=40, packed=True),
+    dict(name="pipe_256_256_s33", B=2, Cin=256, Cout=256, T=160, s_lo=33, s_hi=34, res=True, packed=True),
+    dict(name="pipe_256_768_minus128", B=1, Cin=256, Cout=768, T=480, wmin=-128, packed=True),
+]
+
+
+@pytest.mark.parametrize("kw", PIPE, ids=[c["name"] for c in PIPE])
+def test_pipelined_pointwise_layers(kw):
+    assert run_layer_case(layer_case(**kw)) == "pw_pipe"
+
+
+@pytest.mark.parametrize("slow_passes", [(1,), (0,), (1, 2), (0, 3)])
+def test_pipelined_pointwise_mixed_rescale_forms(slow_passes):
+    """Passes whose s values are all >= 33 are pipelined, the others take the 64-bit form right
+    after their own loop: every order of the two kinds, with a residual."""
+    op, p, x, r, packed = layer_case(name="pipe_mixed", B=1, Cin=256, Cout=1024, T=320, res=True, packed=True)
+    for ps in slow_passes:
+        p["s"][256 * ps:256 * (ps + 1)] = draw(99 + ps, (256,), 20, 32, np.int32)
+    assert run_layer_case((op, p, x, r, packed)) == "pw_pipe"
+
+
 def test_benchmark_shapes_use_the_matrix_core_kernels():
     """The fast kernels, not the generic fallback, serve every op of the benchmark networks."""
     for cfg in range(5):
@@ -174,9 +227,11 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
                 # the pipelined kernel needs at least 3 rows per wave (4 waves per channel)
                 want = "dw_pipe" if net.B >= 12 else "dw_mfma"
             elif o.k == 1 and o.Tin % 16 == 0:
-                # weights-in-registers kernel for the instantiated widths, else the tile kernels
+                # pipelined / weights-in-registers kernels for the instantiated widths, else the tile kernels
                 nt = {4: 4 if o.Cout > 256 else 2, 8: 4}.get(o.Cin // 64 if o.Cin % 64 == 0 else 0)
-                if nt and o.Cout >= 64 * nt:
+                if o.Cin in (256, 512) and 256 <= o.Cout <= 2048:
+                    want = "pw_pipe"          # pipelined-epilogue kernel for the instantiated widths
+                elif nt and o.Cout >= 64 * nt:
                     want = "pw_stream"
                 elif o.Cin % 128 == 0 and o.Cin <= 1024:
                     want = "pw_tile"
