@@ -38,6 +38,9 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 constexpr int kStoreThrough = 17;
 constexpr int NT = 2;           // 16-channel columns per wave and pass
 constexpr int ROWS = 16 * NT;   // output channels of a wave and pass
+constexpr int LOOK = 4;         // weight chunks requested ahead of the one being multiplied
+constexpr int LOOKX = 3;        // activation chunks requested ahead in pass 0
+constexpr int kMaxMT = 7;       // groups per tile: two accumulator sets of 8 groups would not fit the registers
 constexpr int MAXP = 8;         // passes (Cout <= 2048): bounds the constants parked in LDS
 
 struct PwpGeom {
@@ -72,6 +75,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   extern __shared__ __align__(128) unsigned char xs[];
   constexpr int NB = MT * NT;                     // epilogue blocks of a pass
   static_assert(KCH == 4 || KCH == 8, "pieces per product");
+  static_assert(KCH % LOOK == 0, "ring slot of a chunk");
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -98,7 +102,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   const uint32_t resmask = has_res ? 0xffffffffu : 0u;
 
   int seq = 0;                                   // vector-memory requests issued by this wave
-  int mark_r[2] = {0, 0}, mark_c = 0, mark_w[2] = {0, 0}, mark_x[3] = {0, 0, 0};
+  int mark_r[2] = {0, 0}, mark_c = 0, mark_w[LOOK] = {}, mark_x[KCH] = {};
 
   auto issue_residual = [&](int ps, int par) __attribute__((always_inline)) {   // residual rows of pass ps -> stage[par]
     if (has_res) {
@@ -117,7 +121,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   const int Q = P * KCH;
   const v4i wrsrc = make_rsrc(p.w, (uint32_t)g.co16n * (uint32_t)KCH * 1024u);
   const uint32_t wlane = (uint32_t)lane * 16;
-  v4i wb[2][NT];
+  v4i wb[LOOK][NT];                               // ring of weight chunks, LOOK chunks ahead of the products
   auto issue_w = [&](int q, int h) __attribute__((always_inline)) {
     q = q < Q - 1 ? q : Q - 1;
     const int ps = q / KCH, kc = q - ps * KCH;
@@ -130,8 +134,8 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     mark_w[h] = seq;
   };
 
-  // ---- requests of the start: residual of pass 0, constants of all passes, then weights of
-  // chunks 0 and 1 in between the activation chunks (the first products need only 64 channels)
+  // ---- requests of the start: residual of pass 0, constants of all passes, then the first weight
+  // and activation chunks (the first products need only 64 channels)
   issue_residual(0, 0);
   for (int ps = 0; ps < P; ++ps) {
 #pragma unroll
@@ -147,23 +151,24 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     }
   }
   mark_c = seq;
-  {
-    const int r = 8 * wave + (lane >> 3);
-    const int8_t* src = p.x + (int64_t)b_l * p.xbs + (int64_t)r * p.Tin + 16 * t16_l;
-    const int64_t step = (int64_t)64 * p.Tin;
-    unsigned char* dst = xs + 8 * wave * 128;
-    issue_w(0, 0);
-    if (u_ok) direct_load16(src, dst);
-    mark_x[0] = ++seq;
-    issue_w(1, 1);
+  // Activation chunk kc of this wave: rows 64 kc + 8 wave + (0..7).  Only the first LOOKX chunks are
+  // requested here, chunk kc + LOOKX during chunk step kc of pass 0: all workgroups start
+  // together, and a request waits behind everything that entered the memory system before it,
+  // so what is multiplied first has to be asked for first chip-wide.
+  const int8_t* const xsrc = p.x + (int64_t)b_l * p.xbs + (int64_t)(8 * wave + (lane >> 3)) * p.Tin + 16 * t16_l;
+  const int64_t xstep = (int64_t)64 * p.Tin;
+  auto issue_x = [&](int kc) __attribute__((always_inline)) {
+    if (u_ok) direct_load16(xsrc + kc * xstep, xs + 8 * wave * 128 + kc * 8192);
+    mark_x[kc] = ++seq;
+  };
+  issue_w(0, 0);
+  issue_x(0);
+  issue_w(1, 1);
+  issue_x(1);
 #pragma unroll
-    for (int kc = 1; kc < KCH; ++kc) {
-      if (u_ok) direct_load16(src + kc * step, dst + kc * 8192);
-      ++seq;
-      if (kc == 1) mark_x[1] = seq;
-    }
-    mark_x[2] = seq;                              // all of the tile
-  }
+  for (int q = 2; q < LOOK; ++q) issue_w(q, q);
+#pragma unroll
+  for (int kc = 2; kc < LOOKX; ++kc) issue_x(kc);
 
   // per-lane constants of the transpose reads, staging accesses and row stores (see pw_tile.hip)
   const int l16 = lane & 15, j = l16 >> 1;
@@ -262,31 +267,39 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
 
 #pragma unroll
     for (int kk = 0; kk < KCH; ++kk) {
-      const int h = kk & 1;                       // KCH is even: the buffer parity restarts per pass
+      const int h = kk % LOOK;                    // KCH is a multiple of LOOK: the ring restarts per pass
       // weights of this chunk and, in pass 0, the activation chunk(s) needed so far
       if (FIRST) {
         {
-          const int mw = mark_w[h], mx = mark_x[kk < 2 ? kk : 2];   // (by value: no references to the marks)
+          const int mw = mark_w[h], mx = mark_x[kk];   // (by value: no references to the marks)
           wait_vm_dyn(seq - (mw > mx ? mw : mx));
         }
-      } else if (kk < 2) {
+      } else if (kk < LOOK) {
         wait_vm_dyn(seq - mark_w[h]);
       } else {
-        wait_vm<NT>();                            // only the next chunk's weights are younger
+        wait_vm<(LOOK - 1) * NT>();               // only the following chunks' weights are younger
       }
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) tie(wb[h][nt]);
-      if (FIRST && kk <= 2) __syncthreads();      // publishes the other waves' rows of the chunk(s)
+      if (FIRST) {
+        __syncthreads();                          // publishes the other waves' rows of the chunk
+        if (kk + LOOKX < KCH) issue_x(kk + LOOKX);
+      }
       {
         const unsigned char* ab = xs + kk * 8192;
-        v2i a0 = lds_read_tr8(ab + abase);
-        v2i a1 = lds_read_tr8(ab + abase + 4096);
+        // the operand of group mt + 2 is read while groups mt and mt + 1 are multiplied
+        v2i ar[3][2];
+#pragma unroll
+        for (int q = 0; q < 2 && q < MT; ++q) {
+          ar[q][0] = lds_read_tr8(ab + (abase ^ (uint32_t)(q << 4)));
+          ar[q][1] = lds_read_tr8(ab + (abase ^ (uint32_t)(q << 4)) + 4096);
+        }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          const v4i a = {a0.x, a0.y, a1.x, a1.y};
-          if (mt + 1 < MT) {
-            a0 = lds_read_tr8(ab + (abase ^ (uint32_t)((mt + 1) << 4)));
-            a1 = lds_read_tr8(ab + (abase ^ (uint32_t)((mt + 1) << 4)) + 4096);
+          const v4i a = {ar[mt % 3][0].x, ar[mt % 3][0].y, ar[mt % 3][1].x, ar[mt % 3][1].y};
+          if (mt + 2 < MT) {
+            ar[(mt + 2) % 3][0] = lds_read_tr8(ab + (abase ^ (uint32_t)((mt + 2) << 4)));
+            ar[(mt + 2) % 3][1] = lds_read_tr8(ab + (abase ^ (uint32_t)((mt + 2) << 4)) + 4096);
           }
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt) {
@@ -302,7 +315,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
           if (!PREV) __builtin_amdgcn_sched_barrier(0);
         }
       }
-      issue_w(ps * KCH + kk + 2, h);
+      issue_w(ps * KCH + kk + LOOK, h);
     }
     if (PREV) store_rows(ps - 1, par ^ 1);       // (the caller counts these requests)
   };
@@ -379,14 +392,14 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   // per-tile overhead worth about one group
   double best = 1e300;
   c.MT = 7;
-  for (int MT = 4; MT <= 8; ++MT) {
+  for (int MT = 4; MT <= kMaxMT; ++MT) {
     const int64_t tiles = (G + MT - 1) / MT;
     const double cost = (double)((tiles + cus - 1) / cus) * (MT + 1.0);
     if (cost < best - 1e-9) { best = cost; c.MT = MT; }
   }
   if (const char* e = getenv("QASR_PWP_MT")) {            // tuning override
     const int mt = atoi(e);
-    if (mt >= 4 && mt <= 8) c.MT = mt;
+    if (mt >= 4 && mt <= kMaxMT) c.MT = mt;
   }
   return lds_bytes(c.KCH) <= 160 * 1024;
 }
@@ -422,8 +435,8 @@ hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st) {
   Choice c;
   if (!pick(p, c, num_cus())) return hipErrorInvalidValue;
 #define QASR_CASE(M, K) if (c.MT == M && c.KCH == K) return launch_t<M, K>(p, st);
-  QASR_CASE(4, 4) QASR_CASE(5, 4) QASR_CASE(6, 4) QASR_CASE(7, 4) QASR_CASE(8, 4)
-  QASR_CASE(4, 8) QASR_CASE(5, 8) QASR_CASE(6, 8) QASR_CASE(7, 8) QASR_CASE(8, 8)
+  QASR_CASE(4, 4) QASR_CASE(5, 4) QASR_CASE(6, 4) QASR_CASE(7, 4)
+  QASR_CASE(4, 8) QASR_CASE(5, 8) QASR_CASE(6, 8) QASR_CASE(7, 8)
 #undef QASR_CASE
   return hipErrorInvalidValue;
 }
