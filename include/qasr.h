@@ -146,11 +146,26 @@ size_t qasr_encoder_workspace_bytes(const qasr_encoder* e);
 qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same forward as a HIP graph: one launch replays all n_ops kernels with the pointers given
+ * here (x, y and workspace must stay valid and in place as long as the graph is used; their
+ * contents may change between launches).  qasr_encoder_graph_create runs one ordinary forward on
+ * a stream of its own (so y and the workspace are written), captures a second one, instantiates
+ * it and returns the handle in *out (HOST); it synchronises and allocates, so call it at set-up.
+ * qasr_encoder_graph_launch enqueues one replay on `stream` and returns.  The encoder must
+ * outlive the graph.  Errors as for qasr_encoder_forward. */
+typedef struct qasr_encoder_graph qasr_encoder_graph;
+qasr_status qasr_encoder_graph_create(const qasr_encoder* e, const int8_t* x, int8_t* y,
+                                      void* workspace, size_t workspace_bytes,
+                                      qasr_encoder_graph** out);
+qasr_status qasr_encoder_graph_launch(qasr_encoder_graph* g, void* stream);
+void qasr_encoder_graph_destroy(qasr_encoder_graph* g);
+
 /* Same as qasr_encoder_forward, but brackets every op with HIP events, waits for completion and
  * writes each op's device time in milliseconds to op_ms[0..n_ops) (HOST memory): the interval
- * between the events around the op minus the interval of two events recorded back to back with
- * nothing between them (measured in the same call).  For profiling only: it synchronises and
- * creates/destroys events. */
+ * between the events around the op minus an equal share of what the inner events cost (the
+ * forward is also run once without them in the same call; the op times add up to that run's
+ * duration).  For profiling only: it runs the forward twice, synchronises and creates/destroys
+ * events. */
 qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, int8_t* y,
                                        void* workspace, size_t workspace_bytes, void* stream,
                                        float* op_ms);

@@ -72,6 +72,12 @@ def lib():
         L.qasr_encoder_forward.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
         L.qasr_encoder_forward_timed.restype = _i32
         L.qasr_encoder_forward_timed.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float)]
+        L.qasr_encoder_graph_create.restype = _i32
+        L.qasr_encoder_graph_create.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, ctypes.POINTER(_vp)]
+        L.qasr_encoder_graph_launch.restype = _i32
+        L.qasr_encoder_graph_launch.argtypes = [_vp, _vp]
+        L.qasr_encoder_graph_destroy.restype = None
+        L.qasr_encoder_graph_destroy.argtypes = [_vp]
         L.qasr_encoder_num_ops.restype = _i32
         L.qasr_encoder_num_ops.argtypes = [_vp]
         L.qasr_encoder_op_kernel.restype = ctypes.c_char_p
@@ -176,9 +182,40 @@ class Encoder:
                "qasr_encoder_forward_timed")
         return list(ms)
 
+    def graph(self, x, y, workspace) -> "EncoderGraph":
+        """qasr_encoder_graph_create for these buffers (which the returned handle keeps alive)."""
+        return EncoderGraph(self, x, y, workspace)
+
     def close(self):
         if getattr(self, "_h", None):
             lib().qasr_encoder_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class EncoderGraph:
+    """qasr_encoder_graph_* handle: one launch() replays the encoder's forward on (x, y, workspace)."""
+
+    def __init__(self, enc: Encoder, x, y, workspace):
+        self._keep = (enc, x, y, workspace)
+        h = _vp()
+        _check(lib().qasr_encoder_graph_create(enc._h, _ptr(x), _ptr(y), _ptr(workspace),
+                                               workspace.numel() * workspace.element_size(), ctypes.byref(h)),
+               "qasr_encoder_graph_create")
+        self._h = h
+
+    def launch(self):
+        _check(lib().qasr_encoder_graph_launch(self._h, _stream()), "qasr_encoder_graph_launch")
+        return self._keep[2]
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().qasr_encoder_graph_destroy(self._h)
             self._h = None
 
     def __del__(self):

@@ -322,34 +322,85 @@ qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, i
   if (!e || !op_ms) return QASR_ERR_NULL;
   const size_t n = e->ops.size();
   std::vector<hipEvent_t> ev(n + 1, nullptr);
-  hipEvent_t cal[3] = {nullptr, nullptr, nullptr};
+  hipEvent_t cal[2] = {nullptr, nullptr};
   qasr_status st = QASR_OK;
   for (size_t i = 0; i <= n && st == QASR_OK; ++i)
     if (hipEventCreate(&ev[i]) != hipSuccess) st = QASR_ERR_HIP;
-  for (int i = 0; i < 3 && st == QASR_OK; ++i)
+  for (int i = 0; i < 2 && st == QASR_OK; ++i)
     if (hipEventCreate(&cal[i]) != hipSuccess) st = QASR_ERR_HIP;
-  // What two event records cost with nothing between them: recorded back to back ahead of the
-  // ops, the smaller of two intervals is taken off every op's interval.
-  for (int i = 0; i < 3 && st == QASR_OK; ++i)
-    if (hipEventRecord(cal[i], (hipStream_t)stream) != hipSuccess) st = QASR_ERR_HIP;
+  // An event record between two kernels costs device time of its own.  The same forward is run
+  // once without inner events (bracketed by two) and once with them; the difference of the two
+  // totals, spread evenly, is taken off every op's interval, so that the op times add up to the
+  // duration of the undisturbed forward.
+  if (st == QASR_OK && hipEventRecord(cal[0], (hipStream_t)stream) != hipSuccess) st = QASR_ERR_HIP;
+  if (st == QASR_OK) st = forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+  if (st == QASR_OK && hipEventRecord(cal[1], (hipStream_t)stream) != hipSuccess) st = QASR_ERR_HIP;
   if (st == QASR_OK) st = forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, ev.data());
   if (st == QASR_OK && hipEventSynchronize(ev[n]) != hipSuccess) st = QASR_ERR_HIP;
-  float empty_ms = 0.f;
-  if (st == QASR_OK) {
-    float a = 0.f, b = 0.f;
-    if (hipEventElapsedTime(&a, cal[0], cal[1]) != hipSuccess || hipEventElapsedTime(&b, cal[1], cal[2]) != hipSuccess)
+  float per_event_ms = 0.f;
+  if (st == QASR_OK && n > 0) {
+    float plain = 0.f, evented = 0.f;
+    if (hipEventElapsedTime(&plain, cal[0], cal[1]) != hipSuccess || hipEventElapsedTime(&evented, ev[0], ev[n]) != hipSuccess)
       st = QASR_ERR_HIP;
-    empty_ms = a < b ? a : b;
+    per_event_ms = evented > plain ? (evented - plain) / (float)n : 0.f;
   }
   for (size_t i = 0; i < n && st == QASR_OK; ++i) {
     if (hipEventElapsedTime(&op_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = QASR_ERR_HIP;
-    op_ms[i] = op_ms[i] > empty_ms ? op_ms[i] - empty_ms : 0.f;
+    op_ms[i] = op_ms[i] > per_event_ms ? op_ms[i] - per_event_ms : 0.f;
   }
   for (hipEvent_t v : cal)
     if (v) (void)hipEventDestroy(v);
   for (hipEvent_t v : ev)
     if (v) (void)hipEventDestroy(v);
   return st;
+}
+
+struct qasr_encoder_graph {
+  hipGraphExec_t exec = nullptr;
+};
+
+qasr_status qasr_encoder_graph_create(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
+                                      size_t workspace_bytes, qasr_encoder_graph** out) {
+  if (!e || !out) return QASR_ERR_NULL;
+  *out = nullptr;
+  hipStream_t cap = nullptr;
+  if (hipStreamCreate(&cap) != hipSuccess) return QASR_ERR_HIP;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  // One ordinary forward first: argument checks, and the one-time per-kernel set-up (attribute
+  // calls) that must not happen while the stream is capturing.
+  qasr_status st = forward_impl(e, x, y, workspace, workspace_bytes, cap, nullptr);
+  if (st == QASR_OK && hipStreamSynchronize(cap) != hipSuccess) st = QASR_ERR_HIP;
+  if (st == QASR_OK) {
+    if (hipStreamBeginCapture(cap, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+      st = QASR_ERR_HIP;
+    } else {
+      st = forward_impl(e, x, y, workspace, workspace_bytes, cap, nullptr);
+      const hipError_t ee = hipStreamEndCapture(cap, &graph);      // always ends the capture
+      if (st == QASR_OK && (ee != hipSuccess || !graph)) st = QASR_ERR_HIP;
+    }
+  }
+  if (st == QASR_OK && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) st = QASR_ERR_HIP;
+  if (graph) (void)hipGraphDestroy(graph);
+  (void)hipStreamDestroy(cap);
+  if (st != QASR_OK) return st;
+  qasr_encoder_graph* g = new (std::nothrow) qasr_encoder_graph();
+  if (!g) { (void)hipGraphExecDestroy(exec); return QASR_ERR_HIP; }
+  g->exec = exec;
+  *out = g;
+  return QASR_OK;
+}
+
+qasr_status qasr_encoder_graph_launch(qasr_encoder_graph* g, void* stream) {
+  if (!g || !g->exec) return QASR_ERR_NULL;
+  const hipError_t e = hipGraphLaunch(g->exec, (hipStream_t)stream);
+  return e == hipSuccess ? QASR_OK : hip_status(e);
+}
+
+void qasr_encoder_graph_destroy(qasr_encoder_graph* g) {
+  if (!g) return;
+  if (g->exec) (void)hipGraphExecDestroy(g->exec);
+  delete g;
 }
 
 void qasr_encoder_destroy(qasr_encoder* e) {

@@ -80,6 +80,15 @@ __device__ __forceinline__ int32_t clamp_i8(int32_t v, int32_t lo) {
   return min(127, max(lo, v));
 }
 
+// high 32 bits of the signed 64-bit product, in one instruction whatever the surrounding code
+// looks like (the compiler only forms it when both sign extensions sit in the same basic block;
+// with one of them hoisted out of a loop it expands a 64 x 64 multiply instead)
+__device__ __forceinline__ int32_t mulhi_i32(int32_t a, int32_t b) {
+  int32_t r;
+  asm("v_mul_hi_i32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
 // median of three = clamp(x, lo, hi) for lo <= hi, in one instruction (the compiler only forms it
 // by itself when both bounds are compile-time constants)
 __device__ __forceinline__ int32_t med3_i32(int32_t x, int32_t lo, int32_t hi) {

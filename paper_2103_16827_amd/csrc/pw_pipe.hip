@@ -99,7 +99,6 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   unsigned char* const stage0 = xs + KCH * 8192 + wave * (2 * ROWS * 128);
   unsigned char* const cst0 = xs + KCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
   const bool has_res = p.res != nullptr;
-  const uint32_t resmask = has_res ? 0xffffffffu : 0u;
 
   int seq = 0;                                   // vector-memory requests issued by this wave
   int mark_r[2] = {0, 0}, mark_c = 0, mark_w[LOOK] = {}, mark_x[KCH] = {};
@@ -182,14 +181,14 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   int32_t mc[NT], sh[NT], rnd[NT];                // rescale constants of the pass whose epilogue is pending
 
   // one epilogue block: lane (n, gi) holds frames 16 mt + 4 gi + (0..3) of channel 16 nt + n
-  auto block = [&](int par, int e, auto fast_tag) __attribute__((always_inline)) {
-    constexpr bool FAST = decltype(fast_tag)::value;
+  auto block = [&](int par, int e, auto fast_tag, auto res_tag) __attribute__((always_inline)) {
+    constexpr bool FAST = decltype(fast_tag)::value, RES = decltype(res_tag)::value;
     const int mt = e / NT, nt = e % NT;
     uint32_t* const sp = reinterpret_cast<uint32_t*>(stage0 + par * (ROWS * 128) + nt * 2048 + (sbase ^ (uint32_t)(mt << 4)));
-    const uint32_t rw = *sp & resmask;
+    const uint32_t rw = RES ? *sp : 0u;
     const v4i av = acc[par][mt][nt];
     const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
-    *sp = requant_pack4<FAST, true>(a4, mc[nt], sh[nt], rnd[nt], rw, lo, hi127);
+    *sp = requant_pack4<FAST, RES>(a4, mc[nt], sh[nt], rnd[nt], rw, lo, hi127);
   };
   // The pipelined case (short-form rescale, relu): the block is cut into 8 pieces of 3 to 4 vector
   // instructions, one piece per matrix product of the following pass (two when Cin = 256), so
@@ -202,15 +201,17 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     const int mt = e / NT, nt = e % NT;
     return reinterpret_cast<uint32_t*>(stage0 + par * (ROWS * 128) + nt * 2048 + (sbase ^ (uint32_t)(mt << 4)));
   };
-  auto piece = [&](int par, int pidx) __attribute__((always_inline)) {
+  // (RES false: a layer without residual operand skips the residual words and their additions)
+  auto piece = [&](int par, int pidx, auto res_tag) __attribute__((always_inline)) {
+    constexpr bool RES = decltype(res_tag)::value;
     const int e = pidx >> 3, j = pidx & 7, i = j >> 1;
     const int mt = e / NT, nt = e % NT;
-    if (j == 0) rw_cur = rw_next & resmask;
-    if (j == 4 && e + 1 < NB) rw_next = *stage_word(par, e + 1);
+    if (RES && j == 0) rw_cur = rw_next;
+    if (RES && j == 4 && e + 1 < NB) rw_next = *stage_word(par, e + 1);
     if ((j & 1) == 0) {
-      pt[i] = (uint32_t)(((int32_t)__mulhi(acc[par][mt][nt][i], mc[nt]) + rnd[nt]) >> sh[nt]);
+      pt[i] = (uint32_t)((mulhi_i32(acc[par][mt][nt][i], mc[nt]) + rnd[nt]) >> sh[nt]);
     } else {
-      const int32_t t = (int32_t)pt[i] + (int32_t)(int8_t)(rw_cur >> (8 * i));
+      const int32_t t = (int32_t)pt[i] + (RES ? (int32_t)(int8_t)(rw_cur >> (8 * i)) : 0);
       pt[i] = (uint32_t)min(max(t, 0), 127);
       if (i == 1) p01 = pt[0] | (pt[1] << 8);
       if (i == 3) *stage_word(par, e) = p01 | (pt[2] << 16) | (pt[3] << 24);
@@ -234,10 +235,18 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   // the epilogue of pass ps on its own
   auto epilogue_alone = [&](int ps, int par, auto fast_tag) __attribute__((always_inline)) {
     wait_vm_dyn(seq - mark_r[par]);
+    if (has_res) {
 #pragma unroll
-    for (int e = 0; e < NB; ++e) {
-      block(par, e, fast_tag);
-      if (e & 1) __builtin_amdgcn_sched_barrier(0);         // bounds the live temporaries
+      for (int e = 0; e < NB; ++e) {
+        block(par, e, fast_tag, std::true_type{});
+        if (e & 1) __builtin_amdgcn_sched_barrier(0);       // bounds the live temporaries
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < NB; ++e) {
+        block(par, e, fast_tag, std::false_type{});
+        if (e & 1) __builtin_amdgcn_sched_barrier(0);
+      }
     }
     store_rows(ps, par);
     seq += STORE_REQS;
@@ -246,8 +255,8 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   bool pending = false;       // the pass before awaits its (short-form) epilogue
   // The multiply loop of pass ps into accumulator set par; PREV: the epilogue of pass ps - 1 rides along.
   // (FIRST: pass 0, which also waits for the activation chunks and synchronises the waves)
-  auto multiply = [&](int ps, int par, auto prev_tag, auto first_tag) __attribute__((always_inline)) {
-    constexpr bool PREV = decltype(prev_tag)::value, FIRST = decltype(first_tag)::value;
+  auto multiply = [&](int ps, int par, auto prev_tag, auto first_tag, auto res_tag) __attribute__((always_inline)) {
+    constexpr bool PREV = decltype(prev_tag)::value, FIRST = decltype(first_tag)::value, RES = decltype(res_tag)::value;
     // bias of this pass out of LDS (constants of all passes were requested at the start)
     if (FIRST) wait_vm_dyn(seq - mark_c);
     if (!FIRST) issue_residual(ps, par);      // stage[par] is free: its rows left at the end of pass ps - 1
@@ -262,7 +271,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     }
     if (PREV) {
       wait_vm_dyn(seq - mark_r[par ^ 1]);                   // residual rows of the pass before
-      rw_next = *stage_word(par ^ 1, 0);
+      if (RES) rw_next = *stage_word(par ^ 1, 0);
     }
 
 #pragma unroll
@@ -308,7 +317,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
               constexpr int R = 8 / KCH;          // pieces per product: 8 NB pieces over KCH MT NT products
               const int slot = (kk * MT + mt) * NT + nt;
 #pragma unroll
-              for (int r = 0; r < R; ++r) piece(par ^ 1, slot * R + r);
+              for (int r = 0; r < R; ++r) piece(par ^ 1, slot * R + r, res_tag);
               __builtin_amdgcn_sched_barrier(0);  // one product, its pieces, nothing else
             }
           }
@@ -322,9 +331,12 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   // One pass: multiply, then either leave the epilogue pending for the next pass (short-form
   // rescale and a next pass exists) or do it now.
   auto do_pass = [&](int ps, int par, auto first_tag) __attribute__((always_inline)) {
-    if (decltype(first_tag)::value) multiply(ps, par, std::false_type{}, std::true_type{});
-    else if (pending) multiply(ps, par, std::true_type{}, std::false_type{});
-    else multiply(ps, par, std::false_type{}, std::false_type{});
+    const std::true_type T{};
+    const std::false_type F{};
+    if (decltype(first_tag)::value) multiply(ps, par, F, T, F);
+    else if (pending && has_res) multiply(ps, par, T, F, T);
+    else if (pending) multiply(ps, par, T, F, F);
+    else multiply(ps, par, F, F, F);
     seq += pending ? STORE_REQS : 0;      // rows of the pass before, stored at the end of the loop
     // rescale constants of this pass
     const unsigned char* c = cst0 + ps * (NT * 3 * 64) + 4 * n;

@@ -347,3 +347,31 @@ def test_workspace_errors():
     with pytest.raises(Q.QasrError) as e:
         g.enc.forward(x, g.y, small)
     assert e.value.status == -6
+
+
+def test_encoder_graph_replays_match_eager_forwards():
+    """The forward captured as a HIP graph: several replays, each on new input written into the
+    same buffer, with eager work and synchronisation in between, each checked against the eager
+    forward of the same input (and the first against the oracle)."""
+    net = W.build_config(1)
+    params = W.draw_net_params(net, 5)
+    g = GpuNet(net, params)
+    x = dev(W.draw_input(net, 5))
+    gr = g.enc.graph(x, g.y, g.ws)
+    y_eager = torch.empty_like(g.y)
+    for rep in range(4):
+        say(f"graph replay {rep}")
+        xr = W.draw_input(net, 5 + rep)
+        x.copy_(dev(xr))
+        g.enc.forward(x, y_eager, g.ws)                 # eager work between the replays
+        torch.cuda.synchronize()
+        g.y.zero_()
+        torch.cuda.synchronize()
+        gr.launch()
+        torch.cuda.synchronize()
+        assert torch.equal(g.y, y_eager), f"replay {rep} differs from the eager forward"
+        if rep == 0:
+            ref = oracle.encoder_forward(net, params, xr)
+            assert np.array_equal(g.y.cpu().numpy(), ref)
+    gr.close()
+    g.enc.close()
