@@ -11,8 +11,8 @@
 // products of pass p: a wave issues in order, so vector instructions placed between two products
 // execute while the first one occupies the matrix pipeline.  Every chunk step of the multiply
 // loop (64 input channels: MT transpose-read pairs, 2 MT products) carries its share of the 2 MT
-// epilogue blocks of the pass before, cut into pieces of 3 to 4 vector instructions; scheduling
-// fences pin the pattern   product, piece | product, piece | ...
+// epilogue blocks of the pass before, as steps of three mutually independent vector instructions;
+// scheduling fences pin the pattern   product, step | product, step | ...
 // The rows of pass p - 1 leave at the end of pass p's loop and drain under pass p + 1.  Only the
 // last pass's epilogue is exposed.  A pass whose s values are not all >= 33 (64-bit rescale), or a
 // layer without relu, is not pipelined: its epilogue follows its own loop, as in pw_tile.
@@ -74,7 +74,7 @@ template <int MT, int KCH>
 __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   extern __shared__ __align__(128) unsigned char xs[];
   constexpr int NB = MT * NT;                     // epilogue blocks of a pass
-  static_assert(KCH == 4 || KCH == 8, "pieces per product");
+  static_assert(KCH == 4 || KCH == 8, "epilogue steps per product");
   static_assert(KCH % LOOK == 0, "ring slot of a chunk");
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -190,31 +190,44 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
     *sp = requant_pack4<FAST, RES>(a4, mc[nt], sh[nt], rnd[nt], rw, lo, hi127);
   };
-  // The pipelined case (short-form rescale, relu): the block is cut into 8 pieces of 3 to 4 vector
-  // instructions, one piece per matrix product of the following pass (two when Cin = 256), so
-  // that the vector unit works in the shadow of the matrix pipeline.  Piece j of block e:
-  //   j = 0, 2, 4, 6: t[j/2] = (mulhi(acc[j/2], m) + rnd) >> sh
-  //   j = 1, 3, 5, 7: t[j/2] = clamp(t[j/2] + residual byte j/2, 0, 127), and the packing steps
-  // The residual word of block e + 1 is read during block e (rw_next).
-  uint32_t pt[4], p01 = 0, rw_cur = 0, rw_next = 0;
+  // The pipelined case (short-form rescale, relu): the epilogue of a pass is a stream of 4 NB
+  // "elements" (element x = accumulator register x % 4 of block x / 4), each going through six
+  // one-instruction stages
+  //   S0 h = mulhi(acc, m)   S1 h += rnd   S2 h >>= sh   S3 h += residual byte   S4 h = clamp(h, 0, 127)
+  //   S5 pack into the block's word (and write the word to the staging tile after the 4th element)
+  // Element x enters at step 2x and advances one stage per step, so step t carries three
+  // instructions that belong to three different elements and do not depend on each other; what
+  // an instruction needs was produced at least one matrix product earlier.  One step rides on
+  // every product of the following pass (two when Cin = 256); the last five steps follow the loop.
+  // The residual word of block e + 1 is read while block e is in flight.
+  constexpr int NE = 4 * NB;                      // elements of a pass
+  constexpr int NSTEPS = 2 * NE + 4;              // steps 0 .. 2 (NE - 1) + 5
+  int32_t ph[3] = {0, 0, 0};                      // element x lives in ph[x % 3]
+  uint32_t pword = 0, rw[2] = {0u, 0u};           // pack word of the block at S5; residual word of block e in rw[e & 1]
   auto stage_word = [&](int par, int e) __attribute__((always_inline)) {
     const int mt = e / NT, nt = e % NT;
     return reinterpret_cast<uint32_t*>(stage0 + par * (ROWS * 128) + nt * 2048 + (sbase ^ (uint32_t)(mt << 4)));
   };
-  // (RES false: a layer without residual operand skips the residual words and their additions)
-  auto piece = [&](int par, int pidx, auto res_tag) __attribute__((always_inline)) {
+  // (RES false: a layer without residual operand skips the residual words and stage S3)
+  auto step = [&](int par, int t, auto res_tag) __attribute__((always_inline)) {
     constexpr bool RES = decltype(res_tag)::value;
-    const int e = pidx >> 3, j = pidx & 7, i = j >> 1;
-    const int mt = e / NT, nt = e % NT;
-    if (RES && j == 0) rw_cur = rw_next;
-    if (RES && j == 4 && e + 1 < NB) rw_next = *stage_word(par, e + 1);
-    if ((j & 1) == 0) {
-      pt[i] = (uint32_t)((mulhi_i32(acc[par][mt][nt][i], mc[nt]) + rnd[nt]) >> sh[nt]);
+    const int x0 = t >> 1, x1 = x0 - 1, x2 = x0 - 2;        // the elements at stages (S0|S1), (S2|S3), (S4|S5)
+    if ((t & 1) == 0) {
+      if (x0 < NE) {
+        const int e = x0 >> 2, i = x0 & 3;
+        ph[x0 % 3] = mulhi_i32(acc[par][e / NT][e % NT][i], mc[e % NT]);
+        if (RES && i == 1 && e + 1 < NB) rw[(e + 1) & 1] = *stage_word(par, e + 1);
+      }
+      if (x1 >= 0 && x1 < NE) ph[x1 % 3] >>= sh[(x1 >> 2) % NT];
+      if (x2 >= 0 && x2 < NE) ph[x2 % 3] = min(max(ph[x2 % 3], 0), 127);
     } else {
-      const int32_t t = (int32_t)pt[i] + (RES ? (int32_t)(int8_t)(rw_cur >> (8 * i)) : 0);
-      pt[i] = (uint32_t)min(max(t, 0), 127);
-      if (i == 1) p01 = pt[0] | (pt[1] << 8);
-      if (i == 3) *stage_word(par, e) = p01 | (pt[2] << 16) | (pt[3] << 24);
+      if (x0 < NE) ph[x0 % 3] += rnd[(x0 >> 2) % NT];
+      if (RES && x1 >= 0 && x1 < NE) ph[x1 % 3] += (int32_t)(int8_t)(rw[(x1 >> 2) & 1] >> (8 * (x1 & 3)));
+      if (x2 >= 0 && x2 < NE) {
+        const int e = x2 >> 2, i = x2 & 3;
+        pword = i == 0 ? (uint32_t)ph[x2 % 3] : (pword | ((uint32_t)ph[x2 % 3] << (8 * i)));
+        if (i == 3) *stage_word(par, e) = pword;
+      }
     }
   };
   // rows of pass ps out of stage[par]: lane -> (row 8 it + lane/8, slot lane%8)
@@ -271,7 +284,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     }
     if (PREV) {
       wait_vm_dyn(seq - mark_r[par ^ 1]);                   // residual rows of the pass before
-      if (RES) rw_next = *stage_word(par ^ 1, 0);
+      if (RES) rw[0] = *stage_word(par ^ 1, 0);
     }
 
 #pragma unroll
@@ -314,11 +327,11 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
           for (int nt = 0; nt < NT; ++nt) {
             acc[par][mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, wb[h][nt], acc[par][mt][nt], 0, 0, 0);
             if (PREV) {
-              constexpr int R = 8 / KCH;          // pieces per product: 8 NB pieces over KCH MT NT products
+              constexpr int R = 8 / KCH;          // steps per product: 8 NB steps over KCH MT NT products
               const int slot = (kk * MT + mt) * NT + nt;
 #pragma unroll
-              for (int r = 0; r < R; ++r) piece(par ^ 1, slot * R + r, res_tag);
-              __builtin_amdgcn_sched_barrier(0);  // one product, its pieces, nothing else
+              for (int r = 0; r < R; ++r) step(par ^ 1, slot * R + r, res_tag);
+              __builtin_amdgcn_sched_barrier(0);  // one product, its epilogue steps, nothing else
             }
           }
           if (!PREV) __builtin_amdgcn_sched_barrier(0);
@@ -326,7 +339,11 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
       }
       issue_w(ps * KCH + kk + LOOK, h);
     }
-    if (PREV) store_rows(ps - 1, par ^ 1);       // (the caller counts these requests)
+    if (PREV) {
+#pragma unroll
+      for (int t = 8 * NB; t < NSTEPS; ++t) step(par ^ 1, t, res_tag);     // the last elements drain
+      store_rows(ps - 1, par ^ 1);                 // (the caller counts these requests)
+    }
   };
   // One pass: multiply, then either leave the epilogue pending for the next pass (short-form
   // rescale and a next pass exists) or do it now.
