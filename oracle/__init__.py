@@ -47,6 +47,10 @@ def lib():
         L.qasr_oracle_requant.argtypes = [p, i32, i32, i64, p, p, p, p, u32, p]
         L.qasr_oracle_requant_scalar.restype = i64
         L.qasr_oracle_requant_scalar.argtypes = [i64, i32, i32]
+        L.qasr_oracle_quantize.restype = None
+        L.qasr_oracle_quantize.argtypes = [p, i64, ctypes.c_float, p]
+        L.qasr_oracle_dequantize.restype = None
+        L.qasr_oracle_dequantize.argtypes = [p, i64, ctypes.c_float, p]
         _lib = L
     return _lib
 
@@ -113,6 +117,22 @@ def requant(acc, bias, m, s, residual=None, relu=False) -> np.ndarray:
 
 def requant_scalar(A: int, m: int, s: int) -> int:
     return int(lib().qasr_oracle_requant_scalar(A, m, s))
+
+
+def quantize(x, alpha: float) -> np.ndarray:
+    """Eq. 1 with b = 8: float32 features -> int8 codes in [-127, 127] (same shape)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.empty(x.shape, dtype=np.int8)
+    lib().qasr_oracle_quantize(_ptr(x, np.float32), x.size, alpha, _ptr(q, np.int8))
+    return q
+
+
+def dequantize(q, S: float) -> np.ndarray:
+    """DQ(q, S) = S q in float32 (same shape)."""
+    q = np.ascontiguousarray(q, dtype=np.int8)
+    x = np.empty(q.shape, dtype=np.float32)
+    lib().qasr_oracle_dequantize(_ptr(q, np.int8), q.size, S, _ptr(x, np.float32))
+    return x
 
 
 def run_op(op, p, x, residual=None) -> np.ndarray:

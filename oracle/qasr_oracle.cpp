@@ -21,7 +21,10 @@
 // float64 library convolution at real shapes (exact below 2^53), one-hot / identity / ones
 // closed forms, the (m=2^30, s=30) identity, hand-worked rounding and saturation vectors,
 // and the float dequantised product within 1 LSB.  End-to-end encoder bits at full size
-// are pinned by composition only.
+// are pinned by composition only.  The quantiser / dequantiser at the two ends of the path
+// (bottom of this file) are pinned by hand-worked codes, the round trip over all 255 codes,
+// the half-step error bound, odd symmetry and monotonicity, and a float64 recomputation.
+#include <cmath>
 #include <cstdint>
 #include <cstddef>
 #ifdef _OPENMP
@@ -155,5 +158,30 @@ void qasr_oracle_requant(const int32_t* acc, int B, int C, int64_t T, const int3
 
 // Scalar requant (pre-clamp, no residual), exposed so tests can probe single values.
 int64_t qasr_oracle_requant_scalar(int64_t A, int32_t m, int32_t s) { return requant_one(A, m, s); }
+
+// ---- the steps either side of the integer path (Sec. 2.1, Eq. 1 and the sentence after it)
+//
+// Quantiser  q = Q(x, b, S) = Int(clip(x, -alpha, alpha) / S),  S = alpha / (2^(b-1) - 1),  b = 8,
+// so q lies in [-127, 127].  The paper calls Int "the round operation" and fixes no precision;
+// the reading taken here: single precision throughout (the features are float32), S computed
+// once as alpha / 127 in float32, an IEEE division per element, and Int = round to nearest with
+// ties to even (the default rounding of the floating-point environment).  A NaN feature has no
+// defined code; it is mapped to 0.
+void qasr_oracle_quantize(const float* x, int64_t n, float alpha, int8_t* q) {
+    const float S = alpha / 127.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        float v = x[i];
+        if (v != v) { q[i] = 0; continue; }
+        if (v > alpha) v = alpha;            // clip(x, -alpha, alpha)
+        if (v < -alpha) v = -alpha;
+        const float u = v / S;
+        q[i] = (int8_t)std::nearbyintf(u);   // |u| <= 127 (+ at most one rounding of the division, still 127 after Int)
+    }
+}
+
+// Dequantiser  x~ = DQ(q, S) = S * q  (one float32 multiplication).
+void qasr_oracle_dequantize(const int8_t* q, int64_t n, float S, float* x) {
+    for (int64_t i = 0; i < n; ++i) x[i] = S * (float)q[i];
+}
 
 }  // extern "C"

@@ -310,3 +310,63 @@ def test_config0_oracle_is_not_degenerate():
         flat = o.reshape(-1)
         sat = np.mean((flat == 127) | (flat == -128))
         assert 0.02 < sat < 0.98 and len(set(flat.tolist())) > 100
+
+
+# ----------------------------------------------------------------------------- quantiser / dequantiser
+def test_quantiser_hand_worked_codes(golden):
+    """Eq. 1, b = 8: clip, divide by S = alpha / 127, round to nearest with ties to even."""
+    rows = [(float(a), float(x), int(q)) for a, x, q in golden("quantizer_vectors.txt")]
+    assert len(rows) >= 25
+    for alpha, x, q in rows:
+        got = int(oracle.quantize(np.array([x], dtype=np.float32), alpha)[0])
+        assert got == q, (alpha, x, got, q)
+
+
+def test_quantiser_nan_maps_to_zero_and_codes_stay_in_range():
+    x = np.array([np.nan, 3.0, -np.nan], dtype=np.float32)
+    assert oracle.quantize(x, 10.0).tolist() == [0, 38, 0]          # 3 / (10/127) = 38.1
+    big = randint_array(7, (4096,), -10**6, 10**6, np.int32).astype(np.float32) / 1000.0
+    q = oracle.quantize(big, 3.25)
+    assert q.min() == -127 and q.max() == 127                        # Eq. 1's range, never -128
+
+
+@pytest.mark.parametrize("alpha", [127.0, 1.0, 0.037, 6.5, 1000.0, 2.0 ** -20])
+def test_quantiser_matches_float64_recomputation_away_from_ties(alpha):
+    """The same formula evaluated in float64: identical codes wherever x / S is not within
+    1e-3 of a tie (single-precision division cannot move the quotient that far), and never more
+    than one code apart."""
+    rng = np.random.default_rng(int(alpha * 1000) + 3)
+    x = (rng.standard_normal(200000) * alpha * 0.7).astype(np.float32)
+    q = oracle.quantize(x, alpha).astype(np.int64)
+    S = np.float64(np.float32(alpha) / np.float32(127.0))
+    u = np.clip(x.astype(np.float64), -np.float64(np.float32(alpha)), np.float64(np.float32(alpha))) / S
+    ref = np.rint(u).astype(np.int64)
+    assert np.abs(q - ref).max() <= 1
+    away = np.abs(u - np.floor(u) - 0.5) > 1e-3
+    assert away.sum() > 150000 and np.array_equal(q[away], ref[away])
+
+
+@pytest.mark.parametrize("alpha", [127.0, 1.0, 0.037, 6.5, 2.0 ** -20])
+def test_dequantise_then_quantise_is_the_identity_on_all_codes(alpha):
+    """Q(DQ(q, S), S) = q for every code of Eq. 1's range, DQ(q, S) = S q in single precision."""
+    S = np.float32(alpha) / np.float32(127.0)
+    q = np.arange(-127, 128, dtype=np.int8)
+    xq = oracle.dequantize(q, float(S))
+    assert np.array_equal(xq, (S * q.astype(np.float32)).astype(np.float32))
+    assert xq.dtype == np.float32 and xq[127] == 0.0 and xq[254] > 0 > xq[0]
+    assert np.array_equal(oracle.quantize(xq, alpha), q)
+
+
+def test_quantiser_error_bound_symmetry_and_monotonicity():
+    """|DQ(Q(x)) - clip(x)| <= S / 2 (plus rounding of the two float32 operations), Q(-x) = -Q(x),
+    and Q is non-decreasing in x."""
+    alpha = 4.75
+    S = np.float32(alpha) / np.float32(127.0)
+    x = np.sort((np.random.default_rng(11).standard_normal(100000) * 3.0).astype(np.float32))
+    q = oracle.quantize(x, alpha)
+    back = oracle.dequantize(q, float(S)).astype(np.float64)
+    err = np.abs(back - np.clip(x.astype(np.float64), -alpha, alpha))
+    assert err.max() <= float(S) * 0.5 * (1 + 1e-5)
+    assert err.max() > float(S) * 0.49                               # the bound is attained: not vacuous
+    assert np.array_equal(oracle.quantize(-x, alpha).astype(np.int32), -q.astype(np.int32))
+    assert np.all(np.diff(q.astype(np.int32)) >= 0)
