@@ -115,6 +115,21 @@ qasr_status qasr_requant(const int32_t* acc, int32_t B, int32_t C, int32_t T,
  * Sec. 3 are such lists: QuartzNet, Jasper, Conformer-shaped linear layers).  Slot 0 is the
  * network input `x`; the last op's out_slot is the network output `y`; every other slot
  * lives in the caller's workspace. */
+/* Quantiser at the entrance of the path (the paper's Eq. 1 with b = 8):
+ *   q[i] = Int(clip(x[i], -alpha, alpha) / S),  S = alpha / 127,  q in [-127, 127].
+ * x: n float32 features (device), q: n int8 codes (device), any alignment, same element order
+ * (the [B, C, T] layout of the convolutions is just n = B*C*T here).  Single precision
+ * throughout: S is computed once in float32, the division is correctly rounded, Int rounds to
+ * nearest with ties to even; a NaN feature gives 0.  alpha must be finite and > 0 (and large
+ * enough that alpha / 127 does not underflow), else QASR_ERR_PARAM; n == 0 is a no-op; q must
+ * not overlap x.  Enqueues one kernel on `stream` and returns. */
+qasr_status qasr_quantize(const float* x, size_t n, float alpha, int8_t* q, void* stream);
+
+/* Dequantiser at the exit (the sentence after Eq. 1): x[i] = S * q[i], one float32
+ * multiplication per element.  q: n int8 (device), x: n float32 (device); S finite, else
+ * QASR_ERR_PARAM; n == 0 is a no-op; x must not overlap q. */
+qasr_status qasr_dequantize(const int8_t* q, size_t n, float S, float* x, void* stream);
+
 typedef struct {
   qasr_conv1d_desc d;        /* d.x_batch_stride / y_batch_stride as for qasr_conv1d_int8; flags
                                 must not contain QASR_FLAG_W_PACKED (create packs by itself)         */

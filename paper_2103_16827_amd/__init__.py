@@ -7,5 +7,6 @@ importing the binding fails loudly if the library has not been built.
 """
 from .binding import (  # noqa: F401
     QasrError, lib, conv1d_out_len, conv1d_int8, requant, pack_weights, packed_weight_bytes,
-    conv1d_kernel_name, Encoder, ConvDesc, FLAG_RELU, FLAG_W_PACKED, status_string,
+    conv1d_kernel_name, Encoder, EncoderGraph, ConvDesc, FLAG_RELU, FLAG_W_PACKED, status_string,
+    quantize, dequantize,
 )

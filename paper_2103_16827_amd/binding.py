@@ -64,6 +64,10 @@ def lib():
         L.qasr_pack_weights.argtypes = [dp, _vp, _vp, _vp]
         L.qasr_requant.restype = _i32
         L.qasr_requant.argtypes = [_vp, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _u32, _vp, _vp]
+        L.qasr_quantize.restype = _i32
+        L.qasr_quantize.argtypes = [_vp, ctypes.c_size_t, ctypes.c_float, _vp, _vp]
+        L.qasr_dequantize.restype = _i32
+        L.qasr_dequantize.argtypes = [_vp, ctypes.c_size_t, ctypes.c_float, _vp, _vp]
         L.qasr_encoder_create.restype = _i32
         L.qasr_encoder_create.argtypes = [ctypes.POINTER(_Op), _i32, _i32, ctypes.POINTER(_vp)]
         L.qasr_encoder_workspace_bytes.restype = ctypes.c_size_t
@@ -148,6 +152,18 @@ def requant(acc, bias, m, s, residual, flags, y):
     _check(lib().qasr_requant(_ptr(acc), B, C, T, _ptr(bias), _ptr(m), _ptr(s), _ptr(residual), flags,
                               _ptr(y), _stream()), "qasr_requant")
     return y
+
+
+def quantize(x, alpha: float, q):
+    """qasr_quantize: float32 tensor x -> int8 tensor q of the same number of elements."""
+    _check(lib().qasr_quantize(_ptr(x), x.numel(), alpha, _ptr(q), _stream()), "qasr_quantize")
+    return q
+
+
+def dequantize(q, S: float, x):
+    """qasr_dequantize: int8 tensor q -> float32 tensor x of the same number of elements."""
+    _check(lib().qasr_dequantize(_ptr(q), q.numel(), S, _ptr(x), _stream()), "qasr_dequantize")
+    return x
 
 
 class Encoder:

@@ -3,6 +3,7 @@
 #include "../../include/qasr.h"
 #include "kernels.hpp"
 
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -186,6 +187,26 @@ qasr_status qasr_requant(const int32_t* acc, int32_t B, int32_t C, int32_t T, co
   const hipError_t e = qasr::launch_requant(acc, B, C, T, bias, m, s, residual,
                                             (flags & QASR_FLAG_RELU) ? 1 : 0, y, (hipStream_t)stream);
   return hip_status(e);
+}
+
+qasr_status qasr_quantize(const float* x, size_t n, float alpha, int8_t* q, void* stream) {
+  if (!(alpha > 0.0f) || !std::isfinite(alpha)) return QASR_ERR_PARAM;
+  const float S = alpha / 127.0f;
+  if (!(S > 0.0f)) return QASR_ERR_PARAM;                 // alpha so small that the step underflows
+  if (n == 0) return QASR_OK;
+  if (!x || !q) return QASR_ERR_NULL;
+  if (n > ((size_t)1 << 40)) return QASR_ERR_SHAPE;
+  if (overlaps(q, (int64_t)n, x, 4 * (int64_t)n)) return QASR_ERR_ALIAS;
+  return hip_status(qasr::launch_quantize(x, n, alpha, S, q, (hipStream_t)stream));
+}
+
+qasr_status qasr_dequantize(const int8_t* q, size_t n, float S, float* x, void* stream) {
+  if (!std::isfinite(S)) return QASR_ERR_PARAM;
+  if (n == 0) return QASR_OK;
+  if (!x || !q) return QASR_ERR_NULL;
+  if (n > ((size_t)1 << 40)) return QASR_ERR_SHAPE;
+  if (overlaps(x, 4 * (int64_t)n, q, (int64_t)n)) return QASR_ERR_ALIAS;
+  return hip_status(qasr::launch_dequantize(q, n, S, x, (hipStream_t)stream));
 }
 
 qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slots, qasr_encoder** out) {

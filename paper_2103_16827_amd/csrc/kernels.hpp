@@ -51,4 +51,9 @@ hipError_t launch_pw_stream(const ConvParams& p, hipStream_t st);
 bool pw_pipe_supported(const ConvParams& p);
 hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st);
 
+// Quantiser (Eq. 1, b = 8; S = alpha / 127 from the host) and dequantiser (S * q) at the two ends
+// of the path; n elements, any alignment.
+hipError_t launch_quantize(const float* x, size_t n, float alpha, float S, int8_t* q, hipStream_t st);
+hipError_t launch_dequantize(const int8_t* q, size_t n, float S, float* x, hipStream_t st);
+
 }  // namespace qasr

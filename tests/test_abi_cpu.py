@@ -74,6 +74,24 @@ def test_null_and_alias_rejected_before_any_launch():
     assert Q.packed_weight_bytes(make_desc(1, 128, 32, 10)) == 32 * 128
 
 
+def test_quantiser_arguments_rejected_before_any_launch():
+    L = Q.lib()
+    f = ctypes.c_void_p
+    assert L.qasr_quantize(f(4096), 16, 0.0, f(1 << 20), None) == -3          # alpha must be > 0
+    assert L.qasr_quantize(f(4096), 16, -1.0, f(1 << 20), None) == -3
+    assert L.qasr_quantize(f(4096), 16, float("inf"), f(1 << 20), None) == -3
+    assert L.qasr_quantize(f(4096), 16, float("nan"), f(1 << 20), None) == -3
+    assert L.qasr_quantize(f(4096), 16, 1e-44, f(1 << 20), None) == -3        # alpha / 127 underflows to 0
+    assert L.qasr_quantize(None, 16, 1.0, f(1 << 20), None) == -1
+    assert L.qasr_quantize(f(4096), 16, 1.0, None, None) == -1
+    assert L.qasr_quantize(None, 0, 1.0, None, None) == 0                     # nothing to do
+    assert L.qasr_quantize(f(4096), 16, 1.0, f(4096 + 60), None) == -5        # q inside x
+    assert L.qasr_dequantize(f(4096), 16, float("nan"), f(1 << 20), None) == -3
+    assert L.qasr_dequantize(None, 16, 1.0, f(1 << 20), None) == -1
+    assert L.qasr_dequantize(None, 0, 1.0, None, None) == 0
+    assert L.qasr_dequantize(f(4096 + 8), 16, 1.0, f(4096), None) == -5       # x over q
+
+
 def _ops(specs):
     arr = (_Op * len(specs))()
     for i, (d, i_s, r_s, o_s) in enumerate(specs):

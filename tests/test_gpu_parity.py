@@ -375,3 +375,54 @@ def test_encoder_graph_replays_match_eager_forwards():
             assert np.array_equal(g.y.cpu().numpy(), ref)
     gr.close()
     g.enc.close()
+
+
+# ----------------------------------------------------------------------------- quantiser / dequantiser
+def _features(n, seed, alpha):
+    """Seeded float32 features: mostly inside the clipping range, with exact ties, values at and
+    beyond +-alpha, zeros of both signs, infinities and NaNs mixed in."""
+    raw = randint_array(seed, (n,), -(1 << 20), 1 << 20, np.int32).astype(np.float32)
+    x = raw * np.float32(alpha * 1.3 / (1 << 20))
+    S = np.float32(alpha) / np.float32(127.0)
+    k = randint_array(seed + 1, (n,), -130, 130, np.int32).astype(np.float32)
+    tie = (k + np.float32(0.5)) * S
+    sel = randint_array(seed + 2, (n,), 0, 15, np.int32)
+    x = np.where(sel == 0, tie, x)
+    x = np.where(sel == 1, k * S, x)
+    special = np.array([alpha, -alpha, 0.0, -0.0, np.inf, -np.inf, np.nan, 3 * alpha, -3 * alpha], dtype=np.float32)
+    m = min(n, len(special))
+    x[:m] = special[:m]
+    return x.astype(np.float32)
+
+
+@pytest.mark.parametrize("n,alpha,offset", [
+    (0, 1.0, 0), (1, 1.0, 0), (3, 4.75, 0), (1000003, 4.75, 0), (32 * 64 * 1600, 11.3, 0),
+    (4099, 0.037, 1), (4099, 127.0, 3),      # pointers off the 16- / 4-byte grid: the element-wise path
+])
+def test_quantiser_matches_oracle(n, alpha, offset):
+    say(f"quantise n={n} alpha={alpha} offset={offset}")
+    x = _features(n + offset, 17 + n % 13, alpha)[offset:]
+    ref = oracle.quantize(x, alpha)
+    xd = torch.from_numpy(_features(n + offset, 17 + n % 13, alpha)).cuda()[offset:]
+    qd = torch.full((n + offset + 8,), 99, dtype=torch.int8, device="cuda")
+    Q.quantize(xd, alpha, qd[offset:offset + n])
+    torch.cuda.synchronize()
+    got = qd.cpu().numpy()
+    assert np.array_equal(got[offset:offset + n], ref)
+    assert np.all(got[:offset] == 99) and np.all(got[offset + n:] == 99)      # nothing written outside
+    if n > 1000:
+        assert len(set(ref.tolist())) == 255
+
+
+@pytest.mark.parametrize("n,S,offset", [(0, 1.0, 0), (5, 0.25, 0), (1000003, 0.0371, 0), (32 * 29 * 800, 0.118, 0), (4099, 3.0, 3)])
+def test_dequantiser_matches_oracle(n, S, offset):
+    say(f"dequantise n={n} S={S} offset={offset}")
+    q = randint_array(23 + n % 7, (n + offset,), -128, 127, np.int8)
+    ref = oracle.dequantize(q[offset:], S)
+    qd = torch.from_numpy(q).cuda()
+    xd = torch.full((n + offset + 8,), -7.0, dtype=torch.float32, device="cuda")
+    Q.dequantize(qd[offset:], S, xd[offset:offset + n])
+    torch.cuda.synchronize()
+    got = xd.cpu().numpy()
+    assert np.array_equal(got[offset:offset + n].view(np.uint32), ref.view(np.uint32))   # bit for bit
+    assert np.all(got[:offset] == -7.0) and np.all(got[offset + n:] == -7.0)
