@@ -186,7 +186,8 @@ qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, i
                                        float* op_ms);
 
 /* Number of ops, and the name of the kernel family op i is dispatched to (depthwise:
- * "dw_pipe", "dw_mfma"; pointwise: "pw_stream", "pw_tile", "pw_mfma"; dense: "gemm_mfma";
+ * "dw_pipe", "dw_mfma"; pointwise: "pw_pipe", "pw_stream", "pw_tile", "pw_mfma"; dense:
+ * "conv_pipe", "gemm_mfma";
  * any shape: "conv_generic"; static storage, NULL if i is out of range). */
 int32_t qasr_encoder_num_ops(const qasr_encoder* e);
 const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i);

@@ -69,7 +69,7 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
   return p;
 }
 
-enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwMfma, PwTile, PwStream, PwPipe };
+enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwMfma, PwTile, PwStream, PwPipe, ConvPipe };
 
 Kernel pick_kernel(const ConvParams& p) {
   if (p.depthwise) {
@@ -80,6 +80,7 @@ Kernel pick_kernel(const ConvParams& p) {
   if (qasr::pw_stream_supported(p)) return Kernel::PwStream;
   if (qasr::pw_tile_supported(p)) return Kernel::PwTile;
   if (qasr::pw_mfma_supported(p)) return Kernel::PwMfma;
+  if (qasr::conv_pipe_supported(p)) return Kernel::ConvPipe;
   if (qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
   return Kernel::Generic;
 }
@@ -93,6 +94,7 @@ const char* kernel_name(Kernel k) {
     case Kernel::PwTile: return "pw_tile";
     case Kernel::PwStream: return "pw_stream";
     case Kernel::PwPipe: return "pw_pipe";
+    case Kernel::ConvPipe: return "conv_pipe";
     default: return "conv_generic";
   }
 }
@@ -107,6 +109,7 @@ qasr_status launch(const ConvParams& p, hipStream_t st) {
     case Kernel::PwTile: e = qasr::launch_pw_tile(p, st); break;
     case Kernel::PwStream: e = qasr::launch_pw_stream(p, st); break;
     case Kernel::PwPipe: e = qasr::launch_pw_pipe(p, st); break;
+    case Kernel::ConvPipe: e = qasr::launch_conv_pipe(p, st); break;
     default: e = qasr::launch_conv_generic(p, st); break;
   }
   return hip_status(e);

@@ -51,6 +51,11 @@ hipError_t launch_pw_stream(const ConvParams& p, hipStream_t st);
 bool pw_pipe_supported(const ConvParams& p);
 hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st);
 
+// Dense convolution (k >= 2) as an implicit GEMM pipelined over (chunk, tap) steps; needs packed
+// weights, Cin % 64 == 0, Cout >= 64, frame counts and strides that are multiples of 4.
+bool conv_pipe_supported(const ConvParams& p);
+hipError_t launch_conv_pipe(const ConvParams& p, hipStream_t st);
+
 // Quantiser (Eq. 1, b = 8; S = alpha / 127 from the host) and dequantiser (S * q) at the two ends
 // of the path; n elements, any alignment.
 hipError_t launch_quantize(const float* x, size_t n, float alpha, float S, int8_t* q, hipStream_t st);

@@ -167,7 +167,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
 #pragma unroll
   for (int q = 2; q < LOOK; ++q) issue_w(q, q);
 #pragma unroll
-  for (int kc = 2; kc < LOOKX; ++kc) issue_x(kc);
+  for (int kc = 2; kc < LOOKX && kc < KCH; ++kc) issue_x(kc);
 
   // per-lane constants of the transpose reads, staging accesses and row stores (see pw_tile.hip)
   const int l16 = lane & 15, j = l16 >> 1;

@@ -188,6 +188,16 @@ def test_pipelined_depthwise_row_and_split_choices(rs, monkeypatch):
     assert run_layer_case(layer_case(name="dwp_rs", B=48, Cin=8, Cout=8, T=400, k=51, dw=True)) == "dw_pipe"
 
 
+# Dense convolutions through the older implicit-GEMM kernel too (the fallback of conv_pipe).
+DENSE = [c for c in REAL if c.get("k", 1) > 1 and not c.get("dw") and c.get("packed")]
+
+
+@pytest.mark.parametrize("kw", DENSE, ids=[c["name"] for c in DENSE])
+def test_dense_layers_through_the_unpipelined_kernel(kw, monkeypatch):
+    monkeypatch.setenv("QASR_NO_CONV_PIPE", "1")
+    assert run_layer_case(layer_case(**kw)) in ("gemm_mfma", "conv_generic")
+
+
 # The pipelined pointwise kernel: 2..8 passes of 256 output channels, a last pass that only some
 # waves take part in, rows that leave a ragged last tile, every epilogue variant.
 PIPE = [
@@ -240,7 +250,9 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
                 else:
                     want = "gemm_mfma"
             else:
-                want = "gemm_mfma"
+                # dense k > 1: the pipelined implicit GEMM; pointwise on rows that are not a
+                # multiple of 16 frames: the older one
+                want = "conv_pipe" if o.k > 1 else "gemm_mfma"
             assert name == want, (cfg, o.name, name)
 
 
