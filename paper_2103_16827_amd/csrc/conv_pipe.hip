@@ -18,10 +18,14 @@
 //   - the global loads of chunk c + 1 are issued when chunk c starts, their transposition and LDS
 //     writes (into the other of two LDS buffers) happen in the middle of chunk c's taps, under
 //     the matrix products; one barrier per chunk, at its end.
-// Every wave still streams its own weights from L2 (1 KiB per MT products), which is what bounds
-// the big layers: staging the weights of a step in LDS for all waves would be the next step.
+// Every wave streams its own weights from L2 (1 KiB per MT products); loading the same weights in
+// all four waves (a timing experiment with wrong results) changed nothing, so that stream is not
+// what bounds the kernel.  Small layers are bound by the number of workgroups instead: the tile
+// (16 MT frames x 64 NT channels per wave) is chosen per layer by a small occupancy model.
 #include "kernels.hpp"
 
+#include <cmath>
+#include <cstdio>
 #include <cstdlib>
 
 namespace qasr {
@@ -31,8 +35,7 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kXS = 80;       // LDS row pitch in bytes: 64 channels + 16 pad
-constexpr int NT = 4;         // 16-channel columns per wave
-constexpr int NBLK = 6;       // 4x4 blocks per thread and chunk at most: rows <= 384
+constexpr int kMaxRows = 256; // one 4-frame x 16-channel unit per thread and chunk
 
 struct CpGeom {
   int n_tt, n_co;     // frame tiles per batch item, channel tiles
@@ -41,20 +44,7 @@ struct CpGeom {
   int co16n;          // ceil(Cout / 16)
 };
 
-__device__ __forceinline__ void transpose4x4(uint32_t r0, uint32_t r1, uint32_t r2, uint32_t r3,
-                                             uint32_t (&c)[4]) {
-  // r_e = 4 consecutive frames of channel e  ->  c_f = 4 consecutive channels of frame f
-  const uint32_t lo01 = __builtin_amdgcn_perm(r1, r0, 0x05010400u);
-  const uint32_t hi01 = __builtin_amdgcn_perm(r1, r0, 0x07030602u);
-  const uint32_t lo23 = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
-  const uint32_t hi23 = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
-  c[0] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
-  c[1] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
-  c[2] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
-  c[3] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
-}
-
-template <int MT>
+template <int MT, int NT>
 __global__ __launch_bounds__(256) void conv_pipe_kernel(ConvParams p, CpGeom g) {
   extern __shared__ __align__(16) unsigned char xs[];   // [2 buffers][rows][kXS]
   constexpr int TM = 16 * MT, TN = 64 * NT;
@@ -78,54 +68,71 @@ __global__ __launch_bounds__(256) void conv_pipe_kernel(ConvParams p, CpGeom g) 
   const int8_t* xb = p.x + (int64_t)b * p.xbs;
 
   // ---- activation chunk kc: global -> registers (issue), registers -> LDS transposed (commit).
-  // Thread-owned 4x4 blocks: block index blk = tid + 256 i covers frames 4 fq..+4 of channels
-  // 4 cq..+4 of the chunk.
-  const int nfq = g.rows >> 2;                      // frame quads per chunk
-  const int nblk = 16 * nfq;                        // 4x4 blocks per chunk
-  uint32_t xr[NBLK][4];
+  // A thread owns one unit of the chunk: frames 4 fq..+4 of the 16 channels that make one 16-byte
+  // column group cg of the LDS rows (four 4x4 byte blocks, channel quads 2cg, 2cg+1, 2cg+8,
+  // 2cg+9 in the operand order).  It writes four 16-byte rows; lanes with consecutive fq are
+  // 320 bytes apart, which is 16 banks, so the four rows are written in an order rotated by
+  // (fq >> 2) & 3: then 16 consecutive lanes cover all 64 banks.  The rotation costs nothing: it
+  // is folded into the byte selectors of the first transposition stage.
+  const int nfq = g.rows >> 2;                      // frame quads per chunk (<= 64)
+  const int u_fq = tid % nfq, u_cg = tid / nfq;
+  const int rot = (u_fq >> 2) & 3;
+  const int u_f = fa + 4 * u_fq;                    // first input frame of the unit
+  const bool u_on = u_cg < 4 && u_f >= 0 && u_f < p.Tin;
+  const uint32_t xoff = u_on ? (uint32_t)(8 * u_cg * p.Tin + u_f) : 0u;   // (Cin Tin < 2^31)
+  uint32_t sel_lo, sel_hi;                          // frames rot, rot+1 | rot+2, rot+3 of two rows
+  {
+    const uint32_t f0s = rot, f1s = (rot + 1) & 3, f2s = (rot + 2) & 3, f3s = (rot + 3) & 3;
+    sel_lo = f0s | ((4 + f0s) << 8) | (f1s << 16) | ((4 + f1s) << 24);
+    sel_hi = f2s | ((4 + f2s) << 8) | (f3s << 16) | ((4 + f3s) << 24);
+  }
+  uint32_t xr[4][4];
   auto issue_chunk = [&](int kc) __attribute__((always_inline)) {
+    const int8_t* base = xb + (int64_t)(64 * kc) * p.Tin;
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-      const int blk = tid + 256 * i;
-      const int fq = blk % nfq, cq = blk / nfq;
-      const int f = fa + 4 * fq;
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) xr[i][e] = 0;
-      if (blk < nblk && f >= 0 && f < p.Tin) {
-        const int8_t* src = xb + (int64_t)(64 * kc + 4 * cq) * p.Tin + f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) xr[i][e] = *reinterpret_cast<const uint32_t*>(src + (int64_t)e * p.Tin);
+      for (int e = 0; e < 4; ++e) {
+        const int c = 4 * ((i & 1) + 8 * (i >> 1)) + e;
+        xr[i][e] = u_on ? *reinterpret_cast<const uint32_t*>(base + (int64_t)c * p.Tin + xoff) : 0u;
       }
-    }
   };
   auto commit_chunk = [&](int buf) __attribute__((always_inline)) {
-    unsigned char* dst = xs + buf * bufbytes;
+    if (u_cg < 4) {
+      unsigned char* dst = xs + buf * bufbytes + 4 * u_fq * kXS + 16 * u_cg;
+      uint32_t c[4][4];
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-      const int blk = tid + 256 * i;
-      if (blk < nblk) {
-        const int fq = blk % nfq, cq = blk / nfq;
-        uint32_t c[4];
-        transpose4x4(xr[i][0], xr[i][1], xr[i][2], xr[i][3], c);
-        // channels 4 cq..+4 go to the column that the operand order assigns them
-        const int col = 16 * ((cq >> 1) & 3) + 8 * (cq >> 3) + 4 * (cq & 1);
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          *reinterpret_cast<uint32_t*>(dst + (4 * fq + e) * kXS + col) = c[e];
+      for (int i = 0; i < 4; ++i) {
+        // r_e = 4 consecutive frames of channel e  ->  c_e = 4 consecutive channels of frame
+        // (e + rot) & 3
+        const uint32_t lo01 = __builtin_amdgcn_perm(xr[i][1], xr[i][0], sel_lo);
+        const uint32_t hi01 = __builtin_amdgcn_perm(xr[i][1], xr[i][0], sel_hi);
+        const uint32_t lo23 = __builtin_amdgcn_perm(xr[i][3], xr[i][2], sel_lo);
+        const uint32_t hi23 = __builtin_amdgcn_perm(xr[i][3], xr[i][2], sel_hi);
+        c[i][0] = __builtin_amdgcn_perm(lo23, lo01, 0x05040100u);
+        c[i][1] = __builtin_amdgcn_perm(lo23, lo01, 0x07060302u);
+        c[i][2] = __builtin_amdgcn_perm(hi23, hi01, 0x05040100u);
+        c[i][3] = __builtin_amdgcn_perm(hi23, hi01, 0x07060302u);
       }
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        *reinterpret_cast<v4i*>(dst + ((e + rot) & 3) * kXS) =
+            (v4i){(int)c[0][e], (int)c[1][e], (int)c[2][e], (int)c[3][e]};
     }
   };
 
   // ---- weights: step q = (chunk, tap) of the flat contraction, ring of three steps
   const int Q = g.kchunks * p.k;
   int wkc = 0, wj = 0;                              // chunk and tap of the next step to request
-  auto load_w = [&](v4i (&dst)[NT]) __attribute__((always_inline)) {
+  // (the packed buffer is below 2 GiB: a wave-uniform base per step plus a 32-bit lane offset)
+  uint32_t woff[NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int co16 = min((co_w >> 4) + nt, g.co16n - 1);
-      dst[nt] = *reinterpret_cast<const v4i*>(
-          p.w + ((((int64_t)wj * g.co16n + co16) * g.kchunks + wkc) * 64 + lane) * 16);
-    }
+  for (int nt = 0; nt < NT; ++nt)
+    woff[nt] = (uint32_t)((min((co_w >> 4) + nt, g.co16n - 1) * g.kchunks * 64 + lane) * 16);
+  auto load_w = [&](v4i (&dst)[NT]) __attribute__((always_inline)) {
+    const int8_t* wbase = p.w + (int64_t)(wj * g.co16n * g.kchunks + wkc) * 1024;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) dst[nt] = *reinterpret_cast<const v4i*>(wbase + woff[nt]);
     if (wkc * p.k + wj < Q - 1) {                   // (the stream stays on its last step at the end)
       if (++wj == p.k) { wj = 0; ++wkc; }
     }
@@ -151,28 +158,52 @@ __global__ __launch_bounds__(256) void conv_pipe_kernel(ConvParams p, CpGeom g) 
   commit_chunk(0);
   __syncthreads();
 
+  // The A operands (one 16-byte LDS read per 16 frames) go through a ring of three registers,
+  // two reads ahead of the products; the ring runs on across the steps of a chunk, so that a
+  // step's first operands arrive under the previous step's products (a new chunk starts after
+  // the barrier with two exposed reads).
+  auto arow_of = [&](int kc_, int j_) __attribute__((always_inline)) {
+    return xs + (kc_ & 1) * bufbytes + (foff + j_ * p.dil + n * p.stride) * kXS + 16 * gi;
+  };
+  auto read_a = [&](const unsigned char* arow, int mt) __attribute__((always_inline)) {
+    return *reinterpret_cast<const v4i*>(arow + 16 * mt * p.stride * kXS);
+  };
   const int jmid = p.k >> 1;                        // the tap at which the next chunk is committed
   int kc = 0, j = 0;                                // chunk and tap of the current step
   if (g.kchunks > 1) issue_chunk(1);
+  v4i ar[3];
+  ar[0] = read_a(arow_of(0, 0), 0);
+  ar[1] = read_a(arow_of(0, 0), 1);
   for (int q = 0; q < Q; q += 3) {
 #pragma unroll
     for (int u = 0; u < 3; ++u) {
       if (q + u < Q) {
         load_w(wb[(u + 2) % 3]);
-        const unsigned char* arow = xs + (kc & 1) * bufbytes + (foff + j * p.dil + n * p.stride) * kXS + 16 * gi;
+        const unsigned char* arow = arow_of(kc, j);
+        const bool last_tap = j + 1 == p.k;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          const v4i a = *reinterpret_cast<const v4i*>(arow + 16 * mt * p.stride * kXS);
+          if (mt + 2 < MT) {
+            ar[(u * MT + mt + 2) % 3] = read_a(arow, mt + 2);
+          } else if (!last_tap) {
+            ar[(u * MT + mt + 2) % 3] = read_a(arow + p.dil * kXS, mt + 2 - MT);
+          }
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, wb[u][nt], acc[mt][nt], 0, 0, 0);
+            acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ar[(u * MT + mt) % 3], wb[u][nt], acc[mt][nt], 0, 0, 0);
         }
         if (j == jmid && kc + 1 < g.kchunks) commit_chunk((kc + 1) & 1);
-        if (++j == p.k) {
+        if (last_tap) {
           j = 0;
           ++kc;
           __syncthreads();                          // chunk kc is in LDS; chunk kc - 1 has been read by all
           if (kc + 1 < g.kchunks) issue_chunk(kc + 1);
+          if (kc < g.kchunks) {
+            ar[((u + 1) * MT) % 3] = read_a(arow_of(kc, 0), 0);
+            ar[((u + 1) * MT + 1) % 3] = read_a(arow_of(kc, 0), 1);
+          }
+        } else {
+          ++j;
         }
       }
     }
@@ -208,33 +239,51 @@ int lds_rows(const ConvParams& p, int TM) {
   return (((TM - 1) * p.stride + p.dil * (p.k - 1) + 1 + 3) + 3) & ~3;
 }
 
-bool pick(const ConvParams& p, int& MT) {
+// Cycles per (chunk, tap) step on the busiest compute unit, from a small model: a unit holds `occ`
+// workgroups (one wave each per SIMD); a SIMD with w resident waves spends w M cycles in the matrix
+// pipe per step (M = 16 MT NT), a lone wave cannot go below M plus its own latencies (operand reads,
+// weight request, loop), and the operand reads of all waves share the unit's LDS port.
+double step_cycles(int MT, int NT, int64_t blocks) {
+  const int occ = NT == 4 ? 2 : MT > 4 ? 3 : 4;           // bound by registers
+  const double M = 16.0 * MT * NT, alone = M + 150.0, lds = 40.0 * MT;
+  auto T = [&](int64_t w) { return w == 0 ? 0.0 : fmax(fmax((double)w * M, alone), (double)w * lds); };
+  const int64_t n = (blocks + 255) / 256;                 // workgroups on the busiest unit
+  return (double)(n / occ) * T(occ) + T(n % occ);
+}
+
+bool pick(const ConvParams& p, int& MT, int& NT) {
   if (getenv("QASR_NO_CONV_PIPE")) return false;          // tuning: fall through to gemm_mfma
   if (p.depthwise || p.Cin % 64 != 0 || !p.w_packed || p.k < 2) return false;
   if (p.Cout < 64) return false;
   if (p.Tin % 4 != 0 || p.Tout % 4 != 0 || p.xbs % 4 != 0 || p.ybs % 4 != 0) return false;
   if ((uintptr_t)p.x % 4 || (uintptr_t)p.y % 4 || (uintptr_t)p.w % 16 || (p.res && (uintptr_t)p.res % 4))
     return false;
+  // the kernel addresses the packed weights with 32-bit offsets
+  if ((int64_t)p.k * ((p.Cout + 15) / 16) * (p.Cin / 64) * 1024 > 0x7fffffffLL) return false;
   // frames per tile: 96 or 64 (128 would need all 256 registers and leave one wave per SIMD:
-  // measured slower than 96 with two)
-  static const int MTs[] = {6, 4};
+  // measured slower than 96 with two); channels per tile: 256 or 128
+  int force_mt = 0, force_nt = 0;
+  if (const char* e = getenv("QASR_CP_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);   // tuning
+  static const int MTs[] = {8, 7, 6, 5, 4}, NTs[] = {4, 2};
   double best = 1e300;
   bool found = false;
-  for (int mt : MTs) {
-    const int TM = 16 * mt;
-    const int rows = lds_rows(p, TM);
-    if (rows > 64 * NBLK || (int64_t)2 * rows * kXS > 64 * 1024) continue;
-    const int64_t n_tt = (p.Tout + TM - 1) / TM, n_co = (p.Cout + 64 * NT - 1) / (64 * NT);
-    const int64_t blocks = (int64_t)p.B * n_tt * n_co;
-    if (blocks > 0x7fffffffLL) continue;
-    // frames computed per useful frame (tile round-up) and halo read per tile
-    const double cost = (double)(n_tt * TM) / (double)p.Tout * (1.0 + 2.0 / mt);
-    if (cost < best) { best = cost; MT = mt; found = true; }
-  }
+  for (int nt : NTs)
+    for (int mt : MTs) {
+      if ((force_mt && mt != force_mt) || (force_nt && nt != force_nt)) continue;
+      const int TM = 16 * mt;
+      const int rows = lds_rows(p, TM);
+      if (rows > kMaxRows || (int64_t)p.Cin * p.Tin > 0x7fffffffLL) continue;
+      const int64_t n_tt = (p.Tout + TM - 1) / TM, n_co = (p.Cout + 64 * nt - 1) / (64 * nt);
+      const int64_t blocks = (int64_t)p.B * n_tt * n_co;
+      if (blocks > 0x7fffffffLL) continue;
+      // halo read and transposed per tile, relative to the products
+      const double cost = step_cycles(mt, nt, blocks) * (1.0 + 0.25 / mt);
+      if (cost < best * 0.999) { best = cost; MT = mt; NT = nt; found = true; }
+    }
   return found;
 }
 
-template <int MT>
+template <int MT, int NT>
 hipError_t launch_t(const ConvParams& p, hipStream_t st) {
   constexpr int TM = 16 * MT, TN = 64 * NT;
   CpGeom g;
@@ -244,22 +293,32 @@ hipError_t launch_t(const ConvParams& p, hipStream_t st) {
   g.kchunks = p.Cin / 64;
   g.co16n = (p.Cout + 15) / 16;
   const int64_t blocks = (int64_t)p.B * g.n_tt * g.n_co;
-  return launch_kernel(conv_pipe_kernel<MT>, dim3((unsigned)blocks), dim3(256),
+  return launch_kernel(conv_pipe_kernel<MT, NT>, dim3((unsigned)blocks), dim3(256),
                        (size_t)2 * g.rows * kXS, st, p, g);
 }
 
 }  // namespace
 
 bool conv_pipe_supported(const ConvParams& p) {
-  int MT;
-  return pick(p, MT);
+  int MT, NT;
+  return pick(p, MT, NT);
 }
 
 hipError_t launch_conv_pipe(const ConvParams& p, hipStream_t st) {
-  int MT;
-  if (!pick(p, MT)) return hipErrorInvalidValue;
-  if (MT == 6) return launch_t<6>(p, st);
-  return launch_t<4>(p, st);
+  int MT, NT;
+  if (!pick(p, MT, NT)) return hipErrorInvalidValue;
+  switch (10 * MT + NT) {
+    case 84: return launch_t<8, 4>(p, st);
+    case 74: return launch_t<7, 4>(p, st);
+    case 64: return launch_t<6, 4>(p, st);
+    case 54: return launch_t<5, 4>(p, st);
+    case 44: return launch_t<4, 4>(p, st);
+    case 82: return launch_t<8, 2>(p, st);
+    case 72: return launch_t<7, 2>(p, st);
+    case 62: return launch_t<6, 2>(p, st);
+    case 52: return launch_t<5, 2>(p, st);
+    default: return launch_t<4, 2>(p, st);
+  }
 }
 
 }  // namespace qasr

@@ -188,6 +188,24 @@ def test_pipelined_depthwise_row_and_split_choices(rs, monkeypatch):
     assert run_layer_case(layer_case(name="dwp_rs", B=48, Cin=8, Cout=8, T=400, k=51, dw=True)) == "dw_pipe"
 
 
+# Every tile of the pipelined dense kernel (16 MT frames x 64 NT channels per wave), on shapes with
+# ragged frame and channel tiles, a residual, a stride and a dilation.
+CP_TILES = ["%d,%d" % (mt, nt) for nt in (4, 2) for mt in (8, 7, 6, 5, 4)]
+CP_SHAPES = [
+    dict(name="cp_k11_res", B=2, Cin=128, Cout=328, T=428, k=11, packed=True, res=True),
+    dict(name="cp_k5_s2_d3", B=1, Cin=64, Cout=200, T=600, k=5, stride=2, dil=3, pad=(6, 6), packed=True, relu=False),
+]
+
+
+@pytest.mark.parametrize("tile", CP_TILES)
+@pytest.mark.parametrize("kw", CP_SHAPES, ids=[c["name"] for c in CP_SHAPES])
+def test_pipelined_dense_tile_choices(kw, tile, monkeypatch):
+    if kw.get("stride", 1) > 1 and tile.startswith("8"):
+        pytest.skip("128 output frames at stride 2 exceed the kernel's 256 LDS rows")
+    monkeypatch.setenv("QASR_CP_TILE", tile)
+    assert run_layer_case(layer_case(**kw)) == "conv_pipe"
+
+
 # Dense convolutions through the older implicit-GEMM kernel too (the fallback of conv_pipe).
 DENSE = [c for c in REAL if c.get("k", 1) > 1 and not c.get("dw") and c.get("packed")]
 
