@@ -51,6 +51,16 @@ def lib():
         L.qasr_oracle_quantize.argtypes = [p, i64, ctypes.c_float, p]
         L.qasr_oracle_dequantize.restype = None
         L.qasr_oracle_dequantize.argtypes = [p, i64, ctypes.c_float, p]
+        L.qasr_oracle_iexp_constants.restype = i32
+        L.qasr_oracle_iexp_constants.argtypes = [ctypes.c_double, i32, p]
+        L.qasr_oracle_iexp.restype = i64
+        L.qasr_oracle_iexp.argtypes = [i64, i32, i64, i64, i64]
+        L.qasr_oracle_sigmoid_code.restype = i64
+        L.qasr_oracle_sigmoid_code.argtypes = [i32, i32, i64, i64, i64]
+        L.qasr_oracle_act.restype = None
+        L.qasr_oracle_act.argtypes = [i32, p, i32, i32, i64, i64, i64, i32, i64, i64, i64, i32, i32, p]
+        L.qasr_oracle_softmax.restype = None
+        L.qasr_oracle_softmax.argtypes = [p, i64, i64, i32, i64, i64, i64, p]
         _lib = L
     return _lib
 
@@ -133,6 +143,47 @@ def dequantize(q, S: float) -> np.ndarray:
     x = np.empty(q.shape, dtype=np.float32)
     lib().qasr_oracle_dequantize(_ptr(q, np.int8), q.size, S, _ptr(x, np.float32))
     return x
+
+
+ACT_SIGMOID, ACT_SWISH, ACT_GLU = 1, 2, 3
+
+
+def iexp_constants(S: float, u: int) -> dict:
+    """Integer constants of the exponential at scale S / 2^u (Sec. 2.2: polynomial activations)."""
+    out = (ctypes.c_int64 * 3)()
+    if lib().qasr_oracle_iexp_constants(float(S), int(u), out) != 0:
+        raise ValueError("unusable scale")
+    return {"u": int(u), "q_ln2": int(out[0]), "q_b": int(out[1]), "q_c": int(out[2])}
+
+
+def iexp(r: int, c: dict) -> int:
+    assert r <= 0
+    return int(lib().qasr_oracle_iexp(int(r), c["u"], c["q_ln2"], c["q_b"], c["q_c"]))
+
+
+def sigmoid_code(q: int, c: dict) -> int:
+    return int(lib().qasr_oracle_sigmoid_code(int(q), c["u"], c["q_ln2"], c["q_b"], c["q_c"]))
+
+
+def act(kind: int, x, c: dict, m: int, s: int) -> np.ndarray:
+    """x int8 [B, C, T] ([B, 2C, T] for GLU) -> int8 [B, C, T]."""
+    x = np.ascontiguousarray(x, dtype=np.int8)
+    B, Cx, T = x.shape
+    C = Cx // 2 if kind == ACT_GLU else Cx
+    y = np.empty((B, C, T), dtype=np.int8)
+    lib().qasr_oracle_act(kind, _ptr(x, np.int8), B, C, T, Cx * T, C * T, c["u"], c["q_ln2"], c["q_b"],
+                          c["q_c"], int(m), int(s), _ptr(y, np.int8))
+    return y
+
+
+def softmax(x, c: dict) -> np.ndarray:
+    """x int32 [rows, L] -> int8 probabilities at scale 2^-7."""
+    x = np.ascontiguousarray(x, dtype=np.int32)
+    rows, L = x.shape
+    y = np.empty((rows, L), dtype=np.int8)
+    lib().qasr_oracle_softmax(_ptr(x, np.int32), rows, L, c["u"], c["q_ln2"], c["q_b"], c["q_c"],
+                              _ptr(y, np.int8))
+    return y
 
 
 def run_op(op, p, x, residual=None) -> np.ndarray:

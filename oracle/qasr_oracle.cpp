@@ -184,4 +184,116 @@ void qasr_oracle_dequantize(const int8_t* q, int64_t n, float S, float* x) {
     for (int64_t i = 0; i < n; ++i) x[i] = S * (float)q[i];
 }
 
+
+// ---- integer-only non-linear activations (Sec. 2.2, last sentence; Sec. 3, first paragraph)
+//
+// The paper states that Sigmoid, Softmax and Swish are computed with integer arithmetic through
+// second-order polynomials, by the procedure of the integer-only BERT work it cites, and gives no
+// formula of its own.  The reading fixed here restates that published procedure:
+//
+//   exp on x <= 0:  x = -z ln2 + p with p in (-ln2, 0], exp(x) = 2^-z exp(p), and
+//                   exp(p) ~ 0.3585 (p + 1.353)^2 + 0.344 on that interval.
+//   On integers r <= 0 at scale S' (x = S' r), with the host-side constants
+//       q_ln2 = floor(ln2 / S'),  q_b = floor(1.353 / S'),  q_c = floor(0.344 / (0.3585 S'^2)):
+//       z = floor(-r / q_ln2),  p = r + z q_ln2,  L = (p + q_b)^2 + q_c,  E = floor(L / 2^z)
+//   (E = 0 once z > 62), so that exp(S' r) ~ 0.3585 S'^2 E.
+//
+//   An int8 code at scale S is first refined to scale S' = S / 2^u (r = q 2^u, exact), because the
+//   floors in the constants are coarse at an 8-bit step.
+//
+//   Sigmoid is the two-way softmax of (x, 0), which needs only exp of -|x|:
+//       E = iexp(-|q| 2^u),  E0 = iexp(0) = q_b^2 + q_c,
+//       sigma_q = floor((q >= 0 ? E0 : E) 2^15 / (E0 + E))          in [0, 2^15], scale 2^-15.
+//   Swish(x) = x sigmoid(x) and GLU(a, g) = a sigmoid(g) are integer products with that code; all
+//   three go back to int8 through the same dyadic rescale as a layer (round half up, one (m, s)
+//   per tensor) and the clamp to [-128, 127]:
+//       sigmoid: v = sigma_q(q);  swish: v = q sigma_q(q);  glu: v = a sigma_q(g).
+//   GLU splits the channel axis in halves, the first half is the value, the second the gate.
+//
+//   Softmax over a row of int32 logits at scale S (refined by u as well):
+//       r_i = (q_i - max_j q_j) 2^u,  E_i = iexp(r_i),  y_i = min(127, floor(E_i 2^7 / sum_j E_j)),
+//   probabilities at scale 2^-7 in int8.
+//
+// Pins (tests, CPU-only): the real polynomial against exp on (-ln2, 0] within 2.2e-3
+// (its three-digit coefficients); iexp against float exp, its exact halving per q_ln2 and monotonicity; the sigmoid code
+// against the float function over all 256 codes, its value at 0 and the complement identity;
+// swish / glu / sigmoid outputs within one code of the rounded float function (all 256 codes, all
+// 65536 pairs); softmax against the float function, shift invariance, the uniform row's closed
+// form, the one-hot limit; hand-worked values at S = 0.1.
+namespace {
+
+struct IExp { int u; int64_t q_ln2, q_b, q_c; };
+
+inline int64_t iexp_one(int64_t r, const IExp& c) {          // r <= 0
+    const int64_t z = (-r) / c.q_ln2;                          // floor: both operands non-negative
+    const int64_t p = r + z * c.q_ln2;                         // in (-q_ln2, 0]
+    const int64_t L = (p + c.q_b) * (p + c.q_b) + c.q_c;
+    return z > 62 ? 0 : L >> z;                                // L >= 0: the shift is floor(L / 2^z)
+}
+
+inline int64_t sigmoid_code_one(int q, const IExp& c) {
+    const int64_t a = q < 0 ? -int64_t(q) : int64_t(q);
+    const int64_t E = iexp_one(-(a << c.u), c);
+    const int64_t E0 = c.q_b * c.q_b + c.q_c;
+    const int64_t num = q >= 0 ? E0 : E;
+    return (num << 15) / (E0 + E);                             // floor: non-negative operands
+}
+
+}  // namespace
+
+// Host-side constants from the real scale (double precision, floor).  Returns 0, or -1 if the
+// scale is unusable (not finite, not positive, u outside [0, 16], q_ln2 < 1 or q_b >= 2^24).
+int qasr_oracle_iexp_constants(double S, int u, int64_t* out /* q_ln2, q_b, q_c */) {
+    if (!(S > 0.0) || !std::isfinite(S) || u < 0 || u > 16) return -1;
+    const double Sr = S / double(int64_t(1) << u);
+    const double ln2 = 0.693147180559945309417232121458;
+    const double ql = std::floor(ln2 / Sr), qb = std::floor(1.353 / Sr);
+    const double qc = std::floor(0.344 / (0.3585 * Sr * Sr));
+    if (!(ql >= 1.0) || !(qb < 16777216.0)) return -1;
+    out[0] = int64_t(ql); out[1] = int64_t(qb); out[2] = int64_t(qc);
+    return 0;
+}
+
+int64_t qasr_oracle_iexp(int64_t r, int u, int64_t q_ln2, int64_t q_b, int64_t q_c) {
+    return iexp_one(r, IExp{u, q_ln2, q_b, q_c});
+}
+
+int64_t qasr_oracle_sigmoid_code(int q, int u, int64_t q_ln2, int64_t q_b, int64_t q_c) {
+    return sigmoid_code_one(q, IExp{u, q_ln2, q_b, q_c});
+}
+
+// kind: 1 sigmoid, 2 swish, 3 glu.  x [B, C (2C for glu), T] with batch stride xbs, y [B, C, T]
+// with batch stride ybs (elements).
+void qasr_oracle_act(int kind, const int8_t* x, int B, int C, int64_t T, int64_t xbs, int64_t ybs,
+                     int u, int64_t q_ln2, int64_t q_b, int64_t q_c, int32_t m, int32_t s, int8_t* y) {
+    const IExp c{u, q_ln2, q_b, q_c};
+    for (int b = 0; b < B; ++b)
+        for (int ch = 0; ch < C; ++ch)
+            for (int64_t t = 0; t < T; ++t) {
+                const int a = x[b * xbs + int64_t(ch) * T + t];
+                int64_t v;
+                if (kind == 1) v = sigmoid_code_one(a, c);
+                else if (kind == 2) v = int64_t(a) * sigmoid_code_one(a, c);
+                else v = int64_t(a) * sigmoid_code_one(x[b * xbs + (int64_t(C) + ch) * T + t], c);
+                y[b * ybs + int64_t(ch) * T + t] = clamp_out(requant_one(v, m, s), false);
+            }
+}
+
+void qasr_oracle_softmax(const int32_t* x, int64_t rows, int64_t L, int u, int64_t q_ln2, int64_t q_b,
+                         int64_t q_c, int8_t* y) {
+    const IExp c{u, q_ln2, q_b, q_c};
+    for (int64_t i = 0; i < rows; ++i) {
+        const int32_t* xr = x + i * L;
+        int64_t mx = xr[0];
+        for (int64_t j = 1; j < L; ++j) if (xr[j] > mx) mx = xr[j];
+        int64_t sum = 0;
+        for (int64_t j = 0; j < L; ++j) sum += iexp_one((int64_t(xr[j]) - mx) << c.u, c);
+        for (int64_t j = 0; j < L; ++j) {
+            const int64_t E = iexp_one((int64_t(xr[j]) - mx) << c.u, c);
+            const int64_t p = (E << 7) / sum;
+            y[i * L + j] = int8_t(p > 127 ? 127 : p);
+        }
+    }
+}
+
 }  // extern "C"

@@ -370,3 +370,145 @@ def test_quantiser_error_bound_symmetry_and_monotonicity():
     assert err.max() > float(S) * 0.49                               # the bound is attained: not vacuous
     assert np.array_equal(oracle.quantize(-x, alpha).astype(np.int32), -q.astype(np.int32))
     assert np.all(np.diff(q.astype(np.int32)) >= 0)
+
+
+# ----------------------------------------------------------------------------- integer activations
+# (Sec. 2.2, last sentence: Sigmoid, Softmax and Swish through second-order polynomials)
+SCALES = [(8.0 / 127, 8), (4.0 / 127, 8), (0.1, 6), (16.0 / 127, 10), (1.0 / 127, 4)]
+
+
+def test_exp_polynomial_error_on_its_interval():
+    """The real-valued polynomial itself, before any integer step."""
+    p = np.linspace(-math.log(2.0), 0.0, 20001)
+    assert np.max(np.abs(0.3585 * (p + 1.353) ** 2 + 0.344 - np.exp(p))) < 2.2e-3
+
+
+def test_iexp_hand_worked_values(golden):
+    c = oracle.iexp_constants(0.1, 0)
+    assert (c["q_ln2"], c["q_b"], c["q_c"]) == (6, 13, 95)
+    for kind, arg, val in golden("iexp_vectors.txt"):
+        got = oracle.iexp(int(arg), c) if kind == "iexp" else oracle.sigmoid_code(int(arg), c)
+        assert got == int(val), (kind, arg)
+
+
+@pytest.mark.parametrize("S,u", SCALES)
+def test_iexp_against_float_exp_and_its_structure(S, u):
+    c = oracle.iexp_constants(S, u)
+    Sr = S / 2 ** u
+    unit = 0.3585 * Sr * Sr
+    assert c["q_ln2"] == math.floor(math.log(2.0) / Sr)
+    assert oracle.iexp(0, c) == c["q_b"] ** 2 + c["q_c"]
+    rs = sorted({-int(v) for v in np.linspace(0, 24.0 / Sr, 4001)}, reverse=True)
+    prev = None
+    for r in rs:
+        E = oracle.iexp(r, c)
+        # 2.2e-3 of the polynomial (on values >= 1/2, so 4.4e-3 relative), the floors of the three constants (relative 1/q each, and
+        # z/q_ln2 accumulated over the z halvings), one unit of the final floor
+        z = -r // c["q_ln2"]
+        tol = (2.2e-3 / 0.5 + 3.0 / c["q_b"] + (z + 1) * 1.0 / c["q_ln2"]) * math.exp(r * Sr) + unit
+        assert abs(E * unit - math.exp(r * Sr)) <= tol, (r, E)
+        assert prev is None or E <= prev            # non-increasing as the argument falls
+        prev = E
+        assert oracle.iexp(r - c["q_ln2"], c) == E >> 1     # exactly halved per q_ln2
+    assert oracle.iexp(-70 * c["q_ln2"], c) == 0
+
+
+@pytest.mark.parametrize("S,u", SCALES)
+def test_sigmoid_code_against_the_float_function(S, u):
+    c = oracle.iexp_constants(S, u)
+    codes = [oracle.sigmoid_code(q, c) for q in range(-128, 128)]
+    ref = [1.0 / (1.0 + math.exp(-S * q)) for q in range(-128, 128)]
+    assert max(abs(a / 32768.0 - b) for a, b in zip(codes, ref)) < 2.5e-3
+    assert codes[128] == 16384                                    # sigmoid(0) = 1/2 exactly
+    assert all(b >= a for a, b in zip(codes, codes[1:]))          # monotone
+    for q in range(1, 128):                                       # sigma(q) + sigma(-q) = 1 up to one floor
+        assert codes[128 + q] + codes[128 - q] in (32767, 32768)
+    assert all(0 <= v <= 32768 for v in codes)
+
+
+def dyadic_of(ratio: float):
+    """(m, s) with m * 2^-s ~ ratio and 2^30 <= m < 2^31 (a test helper, not the method)."""
+    e = math.floor(math.log2(ratio))
+    s = 30 - e
+    return int(round(ratio * 2.0 ** s)), s
+
+
+@pytest.mark.parametrize("S,u", SCALES[:4])
+def test_swish_and_sigmoid_outputs_within_one_code_of_the_float_function(S, u):
+    c = oracle.iexp_constants(S, u)
+    q = np.arange(-128, 128, dtype=np.int8).reshape(1, 1, 256)
+    x = S * q.astype(np.float64)
+    sig = 1.0 / (1.0 + np.exp(-x))
+    # swish at the input's own scale, sigmoid at 2^-7
+    m, s = dyadic_of(1.0 / 32768.0)
+    y = oracle.act(oracle.ACT_SWISH, q, c, m, s).astype(np.int64)
+    assert np.max(np.abs(y - np.clip(np.floor(x * sig / S + 0.5), -128, 127))) <= 1
+    m, s = dyadic_of(128.0 / 32768.0)
+    y = oracle.act(oracle.ACT_SIGMOID, q, c, m, s).astype(np.int64)
+    assert np.max(np.abs(y - np.clip(np.floor(sig * 128.0 + 0.5), -128, 127))) <= 1
+    # swish is negative only for negative inputs and never below its float minimum by more than a code
+    sw = oracle.act(oracle.ACT_SWISH, q, c, *dyadic_of(1.0 / 32768.0)).reshape(-1).astype(np.int64)
+    assert np.all(sw[128:] >= 0) and np.all(sw[:128] <= 0)
+    assert sw.min() >= math.floor(-0.2785 / S) - 1
+
+
+def test_glu_all_pairs_within_one_code_and_halves_are_value_then_gate():
+    S, u = 6.0 / 127, 8
+    c = oracle.iexp_constants(S, u)
+    a, g = np.meshgrid(np.arange(-128, 128), np.arange(-128, 128), indexing="ij")
+    x = np.stack([a.reshape(-1), g.reshape(-1)]).astype(np.int8).reshape(1, 2, -1)   # C = 1
+    m, s = dyadic_of(1.0 / 32768.0)
+    y = oracle.act(oracle.ACT_GLU, x, c, m, s).reshape(-1).astype(np.int64)
+    ref = a.reshape(-1) * (1.0 / (1.0 + np.exp(-S * g.reshape(-1).astype(np.float64))))
+    assert np.max(np.abs(y - np.clip(np.floor(ref + 0.5), -128, 127))) <= 1
+    # a gate far to the right passes the value, far to the left blocks it
+    x2 = np.zeros((2, 2, 3), dtype=np.int8)
+    x2[:, 0] = [5, -7, 100]
+    x2[0, 1] = 127                              # batch item 0: gates far right
+    x2[1, 1] = -128                             # batch item 1: gates far left
+    c2 = oracle.iexp_constants(0.2, 6)
+    y2 = oracle.act(oracle.ACT_GLU, x2, c2, m, s)
+    assert y2[0, 0].tolist() == [5, -7, 100] and y2[1, 0].tolist() == [0, 0, 0]
+    # two channels: channel c is gated by channel C + c, not by its neighbour
+    x3 = np.zeros((1, 4, 1), dtype=np.int8)
+    x3[0, :, 0] = [100, 100, 127, -128]
+    assert oracle.act(oracle.ACT_GLU, x3, c2, m, s)[0, :, 0].tolist() == [100, 0]
+
+
+@pytest.mark.parametrize("S,u,L", [(0.002, 0, 37), (0.01, 2, 400), (1.0 / 64, 4, 9)])
+def test_softmax_against_the_float_function_and_its_invariants(S, u, L):
+    c = oracle.iexp_constants(S, u)
+    x = randint_array(7, (16, L), -int(6 / S), int(6 / S), np.int32)
+    y = oracle.softmax(x, c).astype(np.int64)
+    z = S * x.astype(np.float64)
+    ref = np.exp(z - z.max(axis=1, keepdims=True))
+    ref = ref / ref.sum(axis=1, keepdims=True)
+    # one code of the floor plus the polynomial's relative error on a probability <= 1
+    assert np.max(np.abs(y - ref * 128.0)) <= 1.0 + 128 * 6.0e-3
+    assert np.all(y >= 0) and np.all(y.sum(axis=1) <= 128) and np.all(y.sum(axis=1) >= 128 - L)
+    assert np.array_equal(oracle.softmax(x + 12345, c), y)                    # shift invariance
+    perm = np.argsort(randint_array(8, (L,), 0, 1 << 30, np.int64))
+    assert np.array_equal(oracle.softmax(x[:, perm], c), y[:, perm])          # permutation
+    # order is kept: a larger logit never gets a smaller code
+    i = np.argsort(x[0])
+    assert np.all(np.diff(y[0][i]) >= 0)
+
+
+def test_softmax_closed_forms():
+    c = oracle.iexp_constants(0.01, 2)
+    for L in (1, 2, 3, 5, 128, 200):
+        assert oracle.softmax(np.full((1, L), -77, dtype=np.int32), c)[0].tolist() == [min(127, 128 // L)] * L
+    x = np.full((1, 50), -2_000_000_000, dtype=np.int32)
+    x[0, 17] = 2_000_000_000                                                  # int32 extremes do not wrap
+    y = oracle.softmax(x, c)[0]
+    assert y[17] == 127 and int(np.abs(y).sum()) == 127
+    # two logits ln 3 apart: probabilities 3/4 and 1/4 -> 96 and 32 within a code
+    d = int(round(math.log(3.0) / 0.01))
+    y = oracle.softmax(np.array([[d, 0]], dtype=np.int32), c)[0]
+    assert abs(int(y[0]) - 96) <= 1 and abs(int(y[1]) - 32) <= 1
+
+
+def test_iexp_constants_reject_unusable_scales():
+    for S, u in [(0.0, 0), (-1.0, 0), (float("nan"), 0), (float("inf"), 0), (1.0, 0), (0.1, -1), (0.1, 17), (1e-9, 8)]:
+        with pytest.raises(ValueError):
+            oracle.iexp_constants(S, u)
