@@ -130,6 +130,58 @@ qasr_status qasr_quantize(const float* x, size_t n, float alpha, int8_t* q, void
  * QASR_ERR_PARAM; n == 0 is a no-op; x must not overlap q. */
 qasr_status qasr_dequantize(const int8_t* q, size_t n, float S, float* x, void* stream);
 
+/* Integer-only non-linear activations (Sec. 2.2, last sentence; Sec. 3, first paragraph: Sigmoid,
+ * Softmax and Swish through second-order polynomials, no floating point executed).  The paper
+ * refers to the integer-only Transformer work it cites for the procedure; as restated here:
+ *
+ *   exp(x), x <= 0:  x = -z ln2 + p, p in (-ln2, 0], exp(p) ~ 0.3585 (p + 1.353)^2 + 0.344.
+ *   On integers r <= 0 at scale S' (x = S' r):
+ *       z = floor(-r / q_ln2),  p = r + z q_ln2,  E = floor(((p + q_b)^2 + q_c) / 2^z)  (0 if z > 62)
+ *       q_ln2 = floor(ln2 / S'),  q_b = floor(1.353 / S'),  q_c = floor(0.344 / (0.3585 S'^2)),
+ *   so that exp(S' r) ~ 0.3585 S'^2 E.  An int8 code q at scale S is refined to r = q 2^u at
+ *   S' = S / 2^u first (the floors above are coarse at an 8-bit step).
+ *
+ * qasr_iexp_init derives the three constants on the HOST in double precision.  Errors:
+ * QASR_ERR_NULL; QASR_ERR_PARAM if S is not finite and positive, u is outside [0, 16],
+ * q_ln2 < 1 or q_b >= 2^24. */
+typedef struct {
+  int32_t u;                 /* refinement shift, 0..16                                             */
+  int32_t reserved;          /* 0                                                                   */
+  int64_t q_ln2, q_b, q_c;   /* 1 <= q_ln2; 0 <= q_b < 2^24; 0 <= q_c < 2^48                        */
+} qasr_iexp;
+qasr_status qasr_iexp_init(double S, int32_t u, qasr_iexp* c);
+
+/* Elementwise activations int8 -> int8 built on that exponential:
+ *   sigmoid code, 15 fraction bits (the two-way softmax of (x, 0)):
+ *       E = iexp(-|q| 2^u),  E0 = q_b^2 + q_c,  sigma_q = floor((q >= 0 ? E0 : E) 2^15 / (E0 + E))
+ *   QASR_ACT_SIGMOID: v = sigma_q(q)        QASR_ACT_SWISH: v = q sigma_q(q)
+ *   QASR_ACT_GLU:     v = a sigma_q(g), a = x[b, c, t], g = x[b, C + c, t]  (x has 2C channels)
+ *   y = clamp(floor((v m + 2^(s-1)) / 2^s), -128, 127)   (the layer's dyadic rescale, one (m, s)
+ *   per tensor: m 2^-s = S_v / S_y with S_v = 2^-15 for sigmoid, S 2^-15 for swish and GLU).
+ * x: [B, C, T] ([B, 2C, T] for GLU) int8 device, batch stride x_batch_stride elements (0 => the
+ * dense one); y: [B, C, T] int8 device, batch stride y_batch_stride (0 => C*T).  y may be x
+ * itself (same pointer and same batch stride: in place; GLU then overwrites the value half);
+ * any other overlap is QASR_ERR_ALIAS.  QASR_ERR_PARAM for an unknown kind, m outside [0, 2^31),
+ * s outside [1, 62] or constants outside the ranges above; QASR_ERR_SHAPE for sizes < 1 or a
+ * stride smaller than an item.  Enqueues one kernel on `stream` and returns. */
+enum { QASR_ACT_SIGMOID = 1, QASR_ACT_SWISH = 2, QASR_ACT_GLU = 3 };
+typedef struct {
+  int32_t kind;              /* QASR_ACT_*                                                          */
+  int32_t m, s;              /* dyadic rescale of the result                                        */
+  int32_t reserved;          /* 0                                                                   */
+  qasr_iexp e;               /* exponential at the input's scale                                    */
+} qasr_act;
+qasr_status qasr_act_int8(const qasr_act* a, const int8_t* x, int32_t B, int32_t C, int32_t T,
+                          int64_t x_batch_stride, int64_t y_batch_stride, int8_t* y, void* stream);
+
+/* Softmax over the last axis of int32 logits at the scale of `e` (attention scores):
+ *   r_i = (q_i - max_j q_j) 2^u,  E_i = iexp(r_i),  y_i = min(127, floor(E_i 2^7 / sum_j E_j)),
+ * probabilities at scale 2^-7.  x: [rows, L] int32 device, y: [rows, L] int8 device, dense;
+ * 1 <= L <= 16384 (the 64-bit sum cannot overflow), rows >= 1, else QASR_ERR_SHAPE; y must not
+ * overlap x.  Enqueues one kernel on `stream` and returns. */
+qasr_status qasr_softmax_int32(const qasr_iexp* e, const int32_t* x, int64_t rows, int32_t L,
+                               int8_t* y, void* stream);
+
 typedef struct {
   qasr_conv1d_desc d;        /* d.x_batch_stride / y_batch_stride as for qasr_conv1d_int8; flags
                                 must not contain QASR_FLAG_W_PACKED (create packs by itself)         */
@@ -140,6 +192,11 @@ typedef struct {
   int32_t in_slot;           /* slot read                                                           */
   int32_t res_slot;          /* slot added in the epilogue, or -1                                   */
   int32_t out_slot;          /* slot written; != in_slot, != res_slot, != 0                         */
+  const qasr_act* act;       /* HOST, copied by create, or NULL: activation applied in place to the
+                                layer's output (after the clamp).  GLU needs an even Cout and
+                                leaves its Cout/2 channels in the first half of every batch item
+                                of the slot: the next layer reads them as a channel-prefix view
+                                (Cin = Cout/2, x_batch_stride = Cout*Tout).                        */
 } qasr_op;
 
 typedef struct qasr_encoder qasr_encoder; /* opaque host object */
@@ -157,7 +214,8 @@ size_t qasr_encoder_workspace_bytes(const qasr_encoder* e);
 
 /* Runs every op in order on `stream`.  x: [B,Cin,Tin] of the first op's descriptor; y: output
  * of the last op; workspace: device, 256-byte aligned, >= qasr_encoder_workspace_bytes(e).
- * Enqueues n_ops kernels and returns; allocates nothing; may be captured into a HIP graph. */
+ * Enqueues n_ops kernels (plus one per activation) and returns; allocates nothing; may be
+ * captured into a HIP graph. */
 qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y,
                                  void* workspace, size_t workspace_bytes, void* stream);
 

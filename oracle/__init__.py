@@ -194,6 +194,18 @@ def run_op(op, p, x, residual=None) -> np.ndarray:
                        x_batch_stride=op.x_batch_stride)
 
 
+def apply_act(a: dict, y: np.ndarray) -> np.ndarray:
+    """The activation of an op on its output, as the encoder applies it: in place; GLU leaves its
+    C/2 channels in the first half of the tensor and the gate half as it was."""
+    c = iexp_constants(a["S"], a["u"])
+    r = act(a["kind"], y, c, a["m"], a["s"])
+    if a["kind"] != ACT_GLU:
+        return r
+    out = y.copy()
+    out[:, : y.shape[1] // 2] = r
+    return out
+
+
 def encoder_forward(net, params, x, keep=False):
     """The op list applied in order over activation slots; returns the last op's output
     (and every op's output when keep=True)."""
@@ -203,6 +215,8 @@ def encoder_forward(net, params, x, keep=False):
         xin = slots[op.in_slot]
         res = slots[op.res_slot] if op.res_slot >= 0 else None
         y = run_op(op, p, xin, res)
+        if getattr(op, "act", 0):
+            y = apply_act(p["act"], y)
         slots[op.out_slot] = y
         if keep:
             outs.append(y)

@@ -26,10 +26,23 @@ class ConvDesc(ctypes.Structure):
                 ("x_batch_stride", _i64), ("y_batch_stride", _i64), ("flags", _u32)]
 
 
+ACT_SIGMOID, ACT_SWISH, ACT_GLU = 1, 2, 3
+
+
+class IExp(ctypes.Structure):
+    """Mirror of qasr_iexp."""
+    _fields_ = [("u", _i32), ("reserved", _i32), ("q_ln2", _i64), ("q_b", _i64), ("q_c", _i64)]
+
+
+class Act(ctypes.Structure):
+    """Mirror of qasr_act."""
+    _fields_ = [("kind", _i32), ("m", _i32), ("s", _i32), ("reserved", _i32), ("e", IExp)]
+
+
 class _Op(ctypes.Structure):
     """Mirror of qasr_op."""
     _fields_ = [("d", ConvDesc), ("w", _vp), ("bias", _vp), ("m", _vp), ("s", _vp),
-                ("in_slot", _i32), ("res_slot", _i32), ("out_slot", _i32)]
+                ("in_slot", _i32), ("res_slot", _i32), ("out_slot", _i32), ("act", ctypes.POINTER(Act))]
 
 
 class QasrError(RuntimeError):
@@ -90,6 +103,12 @@ def lib():
         L.qasr_encoder_destroy.argtypes = [_vp]
         L.qasr_conv1d_kernel_name.restype = ctypes.c_char_p
         L.qasr_conv1d_kernel_name.argtypes = [dp]
+        L.qasr_iexp_init.restype = _i32
+        L.qasr_iexp_init.argtypes = [ctypes.c_double, _i32, ctypes.POINTER(IExp)]
+        L.qasr_act_int8.restype = _i32
+        L.qasr_act_int8.argtypes = [ctypes.POINTER(Act), _vp, _i32, _i32, _i32, _i64, _i64, _vp, _vp]
+        L.qasr_softmax_int32.restype = _i32
+        L.qasr_softmax_int32.argtypes = [ctypes.POINTER(IExp), _vp, _i64, _i32, _vp, _vp]
         L.qasr_last_hip_error.restype = ctypes.c_char_p
         L.qasr_last_hip_error.argtypes = []
         L.qasr_status_string.restype = ctypes.c_char_p
@@ -166,16 +185,46 @@ def dequantize(q, S: float, x):
     return x
 
 
+def iexp_init(S: float, u: int) -> IExp:
+    """qasr_iexp_init: integer constants of the exponential at scale S / 2^u."""
+    c = IExp()
+    _check(lib().qasr_iexp_init(S, u, ctypes.byref(c)), "qasr_iexp_init")
+    return c
+
+
+def make_act(kind: int, e: IExp, m: int, s: int) -> Act:
+    return Act(kind, m, s, 0, e)
+
+
+def act_int8(a: Act, x, B: int, C: int, T: int, y, x_batch_stride: int = 0, y_batch_stride: int = 0):
+    """qasr_act_int8: x int8 [B, C, T] ([B, 2C, T] for GLU) -> y int8 [B, C, T]; y may be x."""
+    _check(lib().qasr_act_int8(ctypes.byref(a), _ptr(x), B, C, T, x_batch_stride, y_batch_stride, _ptr(y),
+                               _stream()), "qasr_act_int8")
+    return y
+
+
+def softmax_int32(e: IExp, x, y):
+    """qasr_softmax_int32: x int32 [rows, L] -> y int8 [rows, L] (probabilities at scale 2^-7)."""
+    rows, L = x.shape
+    _check(lib().qasr_softmax_int32(ctypes.byref(e), _ptr(x), rows, L, _ptr(y), _stream()), "qasr_softmax_int32")
+    return y
+
+
 class Encoder:
     """qasr_encoder_* handle.  `ops` is a sequence of (ConvDesc, w, bias, m, s, in_slot, res_slot,
-    out_slot) with torch CUDA tensors, which the handle keeps alive."""
+    out_slot[, Act or None]) with torch CUDA tensors, which the handle keeps alive."""
 
     def __init__(self, ops: Sequence[tuple], n_slots: int):
         self._keep = [o[1:5] for o in ops]
         arr = (_Op * len(ops))()
-        for i, (d, w, bias, m, s, i_s, r_s, o_s) in enumerate(ops):
+        acts = []
+        for i, o in enumerate(ops):
+            d, w, bias, m, s, i_s, r_s, o_s = o[:8]
+            a = o[8] if len(o) > 8 else None
+            if a is not None:
+                acts.append(a)
             arr[i] = _Op(d, w.data_ptr(), bias.data_ptr() if bias is not None else None, m.data_ptr(),
-                         s.data_ptr(), i_s, r_s, o_s)
+                         s.data_ptr(), i_s, r_s, o_s, ctypes.pointer(a) if a is not None else None)
         h = _vp()
         _check(lib().qasr_encoder_create(arr, len(ops), n_slots, ctypes.byref(h)), "qasr_encoder_create")
         self._h = h

@@ -125,6 +125,8 @@ struct qasr_encoder {
     ConvParams p;          // pointers to weights/constants filled in; x / res / y set per forward
     int32_t in_slot, res_slot, out_slot;
     Kernel kernel;
+    bool has_act = false;
+    qasr::ActParams act;   // applied in place to the output when has_act
   };
   std::vector<Op> ops;
   std::vector<size_t> slot_off;   // byte offset of slot i in the workspace (slot 0 unused)
@@ -212,6 +214,69 @@ qasr_status qasr_dequantize(const int8_t* q, size_t n, float S, float* x, void* 
   return hip_status(qasr::launch_dequantize(q, n, S, x, (hipStream_t)stream));
 }
 
+static qasr_status check_iexp(const qasr_iexp* c) {
+  if (!c) return QASR_ERR_NULL;
+  if (c->u < 0 || c->u > 16 || c->q_ln2 < 1 || c->q_b < 0 || c->q_b >= ((int64_t)1 << 24) || c->q_c < 0 ||
+      c->q_c >= ((int64_t)1 << 48))
+    return QASR_ERR_PARAM;
+  return QASR_OK;
+}
+
+static qasr_status check_act(const qasr_act* a) {
+  if (!a) return QASR_ERR_NULL;
+  if (a->kind != QASR_ACT_SIGMOID && a->kind != QASR_ACT_SWISH && a->kind != QASR_ACT_GLU) return QASR_ERR_PARAM;
+  if (a->m < 0 || a->s < 1 || a->s > 62) return QASR_ERR_PARAM;
+  return check_iexp(&a->e);
+}
+
+static qasr::ActParams act_params(int32_t kind, int32_t m, int32_t s, const qasr_iexp& e) {
+  qasr::ActParams p;
+  p.kind = kind; p.m = m; p.s = s; p.u = e.u;
+  p.q_ln2 = e.q_ln2; p.q_b = e.q_b; p.q_c = e.q_c;
+  return p;
+}
+
+qasr_status qasr_iexp_init(double S, int32_t u, qasr_iexp* c) {
+  if (!c) return QASR_ERR_NULL;
+  if (!(S > 0.0) || !std::isfinite(S) || u < 0 || u > 16) return QASR_ERR_PARAM;
+  const double step = std::ldexp(S, -u);                   // S / 2^u, exact
+  const double ln2 = 0.6931471805599453;                    // nearest double to ln 2
+  const double q_ln2 = std::floor(ln2 / step);
+  const double q_b = std::floor(1.353 / step);
+  const double q_c = std::floor(0.344 / (0.3585 * step * step));
+  if (!(q_ln2 >= 1.0) || !(q_b < 16777216.0)) return QASR_ERR_PARAM;
+  c->u = u;
+  c->reserved = 0;
+  c->q_ln2 = (int64_t)q_ln2;
+  c->q_b = (int64_t)q_b;
+  c->q_c = (int64_t)q_c;
+  return QASR_OK;
+}
+
+qasr_status qasr_act_int8(const qasr_act* a, const int8_t* x, int32_t B, int32_t C, int32_t T,
+                          int64_t x_batch_stride, int64_t y_batch_stride, int8_t* y, void* stream) {
+  const qasr_status st = check_act(a);
+  if (st != QASR_OK) return st;
+  if (!x || !y) return QASR_ERR_NULL;
+  if (B < 1 || B > 65535 || C < 1 || T < 1) return QASR_ERR_SHAPE;
+  const int64_t n = (int64_t)C * T, nx = a->kind == QASR_ACT_GLU ? 2 * n : n;
+  const int64_t xbs = x_batch_stride ? x_batch_stride : nx, ybs = y_batch_stride ? y_batch_stride : n;
+  if (xbs < nx || ybs < n) return QASR_ERR_SHAPE;
+  const bool in_place = (const int8_t*)y == x && xbs == ybs;
+  if (!in_place && overlaps(y, (int64_t)(B - 1) * ybs + n, x, (int64_t)(B - 1) * xbs + nx)) return QASR_ERR_ALIAS;
+  return hip_status(qasr::launch_act(act_params(a->kind, a->m, a->s, a->e), x, y, B, n, xbs, ybs, (hipStream_t)stream));
+}
+
+qasr_status qasr_softmax_int32(const qasr_iexp* e, const int32_t* x, int64_t rows, int32_t L, int8_t* y,
+                               void* stream) {
+  const qasr_status st = check_iexp(e);
+  if (st != QASR_OK) return st;
+  if (!x || !y) return QASR_ERR_NULL;
+  if (rows < 1 || L < 1 || L > 16384 || rows > ((int64_t)1 << 40) / L) return QASR_ERR_SHAPE;
+  if (overlaps(y, rows * L, x, 4 * rows * L)) return QASR_ERR_ALIAS;
+  return hip_status(qasr::launch_softmax(act_params(0, 0, 1, *e), x, rows, L, y, (hipStream_t)stream));
+}
+
 qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slots, qasr_encoder** out) {
   if (!ops || !out) return QASR_ERR_NULL;
   if (n_ops < 1 || n_slots < 2) return QASR_ERR_SHAPE;
@@ -234,6 +299,12 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
         o.res_slot < -1 || o.res_slot >= n_slots)
       return QASR_ERR_PARAM;
     if (o.out_slot == o.in_slot || o.out_slot == o.res_slot) return QASR_ERR_PARAM;
+    if (o.act) {
+      const qasr_status as = check_act(o.act);
+      if (as != QASR_OK) return as;
+      if (o.act->kind == QASR_ACT_GLU && (o.d.Cout & 1)) return QASR_ERR_SHAPE;
+      if (o.d.B > 65535) return QASR_ERR_SHAPE;
+    }
     if (i == 0) {
       if (ops[0].in_slot != 0) return QASR_ERR_PARAM;
       slot[0].live = true;
@@ -294,6 +365,10 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     }
     op.p = make_params(&op.d, nullptr, w, o.bias, o.m, o.s, nullptr, nullptr);
     op.kernel = pick_kernel(op.p);
+    if (o.act) {
+      op.has_act = true;
+      op.act = act_params(o.act->kind, o.act->m, o.act->s, o.act->e);
+    }
   }
   if (packed_bytes) {
     const hipError_t se = hipStreamSynchronize(nullptr);
@@ -331,6 +406,12 @@ static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* 
     if (ev) { const hipError_t re = hipEventRecord(ev[i], st); if (re != hipSuccess) return hip_status(re); }
     const qasr_status s = launch(p, st);
     if (s != QASR_OK) return s;
+    if (op.has_act) {
+      const bool glu = op.act.kind == QASR_ACT_GLU;
+      const int64_t n_out = (int64_t)(glu ? p.Cout / 2 : p.Cout) * p.Tout;
+      const hipError_t ae = qasr::launch_act(op.act, p.y, p.y, p.B, n_out, p.ybs, p.ybs, st);
+      if (ae != hipSuccess) return hip_status(ae);
+    }
   }
   if (ev) { const hipError_t re = hipEventRecord(ev[n], st); if (re != hipSuccess) return hip_status(re); }
   return QASR_OK;

@@ -61,4 +61,18 @@ hipError_t launch_conv_pipe(const ConvParams& p, hipStream_t st);
 hipError_t launch_quantize(const float* x, size_t n, float alpha, float S, int8_t* q, hipStream_t st);
 hipError_t launch_dequantize(const int8_t* q, size_t n, float S, float* x, hipStream_t st);
 
+// Integer-only activations (Sec. 2.2: second-order polynomial exponential).  kind 1 sigmoid,
+// 2 swish, 3 GLU; u refines an int8 code to scale S / 2^u; q_ln2, q_b, q_c are the host-side
+// constants of the exponential at that scale; (m, s) the dyadic rescale of the result.
+struct ActParams {
+  int32_t kind, m, s, u;
+  int64_t q_ln2, q_b, q_c;
+};
+// x: B items of n (2 n for GLU: value half, gate half) int8 at stride xbs; y: B items of n int8
+// at stride ybs; y may be x itself when the strides are equal.
+hipError_t launch_act(const ActParams& c, const int8_t* x, int8_t* y, int32_t B, int64_t n, int64_t xbs,
+                      int64_t ybs, hipStream_t st);
+// rows x L int32 logits -> int8 probabilities at scale 2^-7 (kind, m, s unused).
+hipError_t launch_softmax(const ActParams& c, const int32_t* x, int64_t rows, int32_t L, int8_t* y, hipStream_t st);
+
 }  // namespace qasr

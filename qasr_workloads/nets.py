@@ -41,6 +41,7 @@ class OpSpec:
     in_slot: int = 0
     res_slot: int = -1
     out_slot: int = 1
+    act: int = 0                 # 0 none, 1 sigmoid, 2 swish, 3 GLU (applied in place to the output)
 
     @property
     def Tout(self) -> int:
@@ -91,7 +92,7 @@ class _Builder:
         self.n_tensors = 1
 
     def op(self, name, Cout, k=1, stride=1, dilation=1, pad=None, groups=1, relu=True,
-           bias=True, res=-1, Cin=None, x_batch_stride=0, advance=True):
+           bias=True, res=-1, Cin=None, x_batch_stride=0, advance=True, act=0):
         """Append one op reading the running activation; returns its output tensor id."""
         Cin = self.C if Cin is None else Cin
         if pad is None:
@@ -100,7 +101,7 @@ class _Builder:
         out = self.n_tensors
         self.n_tensors += 1
         o = OpSpec(name, Cin, Cout, self.T, k, stride, dilation, pad[0], pad[1], groups,
-                   x_batch_stride, FLAG_RELU if relu else 0, bias, self.cur, res, out)
+                   x_batch_stride, FLAG_RELU if relu else 0, bias, self.cur, res, out, act)
         self.net.ops.append(o)
         if advance:
             self.cur, self.C, self.T = out, Cout, o.Tout
@@ -180,17 +181,24 @@ def jasper(B, T, config_id, Cin=64, widths=(256, 384, 512, 640, 768), kernels=(1
     return b.done()
 
 
-def conformer_shaped(B, T, config_id, d_model=512, d_ff=2048, k=32, layers=17, name="conformer_l_shaped") -> NetSpec:
+ACT_SIGMOID, ACT_SWISH, ACT_GLU = 1, 2, 3
+
+
+def conformer_shaped(B, T, config_id, d_model=512, d_ff=2048, k=32, layers=17, name="conformer_l_shaped",
+                     nonlinear=False) -> NetSpec:
     """Conformer-L-shaped integer linear layers (config 4): per layer ffn1, ffn2, pw1 (d->2d),
     depthwise k on the first d channels of pw1's output (a strided channel-prefix view), pw2.
-    No ReLU, no residual: nonlinearities are identity in this configuration."""
+    No ReLU, no residual.  Nonlinearities are identity in configuration 4 itself; with
+    `nonlinear` the layers carry the integer activations of the architecture: Swish after ffn1
+    and after the depthwise convolution, GLU after pw1 (its d outputs are the prefix view)."""
     b = _Builder(name, config_id, B, d_model, T)
+    sw, glu = (ACT_SWISH, ACT_GLU) if nonlinear else (0, 0)
     for li in range(layers):
-        b.op(f"L{li}.ffn1", d_ff, relu=False)
+        b.op(f"L{li}.ffn1", d_ff, relu=False, act=sw)
         b.op(f"L{li}.ffn2", d_model, relu=False)
-        b.op(f"L{li}.pw1", 2 * d_model, relu=False)
+        b.op(f"L{li}.pw1", 2 * d_model, relu=False, act=glu)
         b.op(f"L{li}.dw", d_model, k=k, groups=d_model, relu=False, bias=False,
-             Cin=d_model, x_batch_stride=2 * d_model * b.T)
+             Cin=d_model, x_batch_stride=2 * d_model * b.T, act=sw)
         b.op(f"L{li}.pw2", d_model, relu=False)
     return b.done()
 
@@ -207,6 +215,8 @@ def build_config(i: int, B: Optional[int] = None) -> NetSpec:
         return jasper(B or 16, 1600, config_id=3)
     if i == 4:
         return conformer_shaped(B or 16, 400, config_id=4)
+    if i == 5:      # not one of the five: configuration 4 with its integer nonlinearities in place
+        return conformer_shaped(B or 16, 400, config_id=5, name="conformer_l_shaped_nonlinear", nonlinear=True)
     raise ValueError(i)
 
 
@@ -222,6 +232,9 @@ def tiny_config(i: int) -> NetSpec:
                       k_pro=3, C_epi=5, k_epi=3, C_epi2=6, n_out=3, name="tiny_jasper")
     if i == 4:
         return conformer_shaped(2, 9, config_id=104, d_model=4, d_ff=8, k=4, layers=2, name="tiny_conformer")
+    if i == 5:
+        return conformer_shaped(2, 9, config_id=105, d_model=4, d_ff=8, k=4, layers=2,
+                                name="tiny_conformer_nonlinear", nonlinear=True)
     raise ValueError(i)
 
 
@@ -238,7 +251,10 @@ def draw_net_params(net: NetSpec, seed: int, m_lo=1 << 30, m_hi=(1 << 31) - 1, s
     """Per-op constants as the offline quantiser would emit them (here: seeded draws).
 
     w int8 U[-127,127] in PyTorch Conv1d order [Cout, Cin/groups, k]; bias int32
-    U[-bias_mag, bias_mag] (default 2^16) or None; m int32 U[2^30, 2^31); s int32 U{36..44}."""
+    U[-bias_mag, bias_mag] (default 2^16) or None; m int32 U[2^30, 2^31); s int32 U{36..44}.
+    An op with an activation also gets "act": the real scale S of its int8 input (U[4, 8] / 127 in
+    steps of 0.01 / 127), the refinement shift u = 8, and the activation's own output rescale
+    (m U[2^30, 2^31), s = 45: a ratio in [2^-15, 2^-14), i.e. about the input's own scale)."""
     out = []
     for i, o in enumerate(net.ops):
         cin_g = 1 if o.depthwise else o.Cin
@@ -249,6 +265,10 @@ def draw_net_params(net: NetSpec, seed: int, m_lo=1 << 30, m_hi=(1 << 31) - 1, s
             "m": randint_array(sd("m"), (o.Cout,), m_lo, m_hi, np.int32),
             "s": randint_array(sd("s"), (o.Cout,), s_lo, s_hi, np.int32),
         }
+        if o.act:
+            r = randint_array(sd("act"), (2,), 0, (1 << 31) - 1, np.int64)
+            p["act"] = {"kind": o.act, "S": (400 + int(r[0]) % 401) / 100.0 / 127.0, "u": 8,
+                        "m": (1 << 30) + int(r[1]) % (1 << 30), "s": 45}
         out.append(p)
     return out
 

@@ -46,9 +46,9 @@ def splitmix64_stream(seed: int, n: int, offset: int = 0) -> np.ndarray:
 def tensor_seed(base_seed: int, config_id: int, op_index: int, kind: str) -> int:
     """Per-tensor stream seed: one splitmix64 mixing step over (base, config, op, kind).
 
-    kind is one of 'x', 'w', 'bias', 'm', 's', 'res', 'acc'.
+    kind is one of 'x', 'w', 'bias', 'm', 's', 'res', 'acc', 'act'.
     """
-    kinds = {"x": 1, "w": 2, "bias": 3, "m": 4, "s": 5, "res": 6, "acc": 7}
+    kinds = {"x": 1, "w": 2, "bias": 3, "m": 4, "s": 5, "res": 6, "acc": 7, "act": 8}
     v = (base_seed & _MASK)
     for part in (config_id + 1, op_index + 1, kinds[kind]):
         v = _mix_py((v + part * _GAMMA) & _MASK)

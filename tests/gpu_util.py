@@ -15,6 +15,13 @@ def desc_of(op, B, flags_extra=0):
                      op.groups, op.x_batch_stride, 0, op.flags | flags_extra)
 
 
+def act_of(a):
+    """Workload activation record -> qasr_act (constants through qasr_iexp_init), or None."""
+    if not a:
+        return None
+    return Q.make_act(a["kind"], Q.iexp_init(a["S"], a["u"]), a["m"], a["s"])
+
+
 def gpu_layer(op, B, p, x, residual=None, packed=False):
     """One op through qasr_conv1d_int8; returns a numpy int8 array."""
     d = desc_of(op, B)
@@ -26,6 +33,10 @@ def gpu_layer(op, B, p, x, residual=None, packed=False):
         d.flags |= Q.FLAG_W_PACKED
     y = torch.full((B, op.Cout, op.Tout), 77, dtype=torch.int8, device="cuda")
     Q.conv1d_int8(d, dev(x), w, dev(p["bias"]), dev(p["m"]), dev(p["s"]), dev(residual), y)
+    if p.get("act"):
+        a = p["act"]
+        Q.act_int8(act_of(a), y, B, op.Cout // 2 if a["kind"] == Q.ACT_GLU else op.Cout, op.Tout, y,
+                   op.Cout * op.Tout, op.Cout * op.Tout)
     torch.cuda.synchronize()
     return y.cpu().numpy()
 
@@ -35,9 +46,10 @@ class GpuNet:
 
     def __init__(self, net, params):
         self.net = net
-        self.dev_params = [{k: dev(v) for k, v in p.items()} for p in params]
-        ops = [(desc_of(o, net.B), dp["w"], dp["bias"], dp["m"], dp["s"], o.in_slot, o.res_slot, o.out_slot)
-               for o, dp in zip(net.ops, self.dev_params)]
+        self.dev_params = [{k: dev(v) for k, v in p.items() if k != "act"} for p in params]
+        ops = [(desc_of(o, net.B), dp["w"], dp["bias"], dp["m"], dp["s"], o.in_slot, o.res_slot, o.out_slot,
+                act_of(p.get("act")))
+               for o, dp, p in zip(net.ops, self.dev_params, params)]
         self.enc = Q.Encoder(ops, net.n_slots)
         self.ws = torch.empty(max(self.enc.workspace_bytes, 256), dtype=torch.int8, device="cuda")
         self.y = torch.empty((net.B, net.Cout, net.Tout), dtype=torch.int8, device="cuda")

@@ -92,10 +92,71 @@ def test_quantiser_arguments_rejected_before_any_launch():
     assert L.qasr_dequantize(f(4096 + 8), 16, 1.0, f(4096), None) == -5       # x over q
 
 
+def test_iexp_constants_on_the_host():
+    c = Q.iexp_init(0.1, 0)                      # floor(6.93), floor(13.53), floor(0.344 / 0.003585)
+    assert (c.u, c.q_ln2, c.q_b, c.q_c) == (0, 6, 13, 95)
+    c = Q.iexp_init(0.1, 3)                      # the same at a step of 0.0125
+    assert (c.u, c.q_ln2, c.q_b, c.q_c) == (3, 55, 108, 6141)
+    L = Q.lib()
+    out = Q.IExp()
+    for S, u in [(0.0, 0), (-1.0, 0), (float("nan"), 0), (float("inf"), 0), (1.0, 0), (0.1, -1), (0.1, 17), (1e-9, 8)]:
+        assert L.qasr_iexp_init(S, u, ctypes.byref(out)) == -3, (S, u)
+    assert L.qasr_iexp_init(0.1, 0, None) == -1
+
+
+def test_activation_arguments_rejected_before_any_launch():
+    L = Q.lib()
+    f = ctypes.c_void_p
+    e = Q.iexp_init(6.0 / 127, 8)
+    ok = Q.make_act(Q.ACT_SWISH, e, 1 << 30, 45)
+    call = lambda a, x, B, C, T, xbs, ybs, y: L.qasr_act_int8(ctypes.byref(a) if a is not None else None, x, B, C, T, xbs, ybs, y, None)
+    assert call(None, f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -1
+    assert call(ok, None, 1, 4, 16, 0, 0, f(1 << 20)) == -1
+    assert call(ok, f(4096), 1, 4, 16, 0, 0, None) == -1
+    assert call(Q.make_act(0, e, 1 << 30, 45), f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -3      # kind
+    assert call(Q.make_act(4, e, 1 << 30, 45), f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -3
+    assert call(Q.make_act(2, e, -1, 45), f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -3           # m
+    assert call(Q.make_act(2, e, 1 << 30, 0), f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -3       # s
+    assert call(Q.make_act(2, e, 1 << 30, 63), f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -3
+    bad = Q.IExp(8, 0, 0, 100, 100)                                                            # q_ln2 < 1
+    assert call(Q.make_act(2, bad, 1 << 30, 45), f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -3
+    bad = Q.IExp(8, 0, 10, 1 << 24, 100)                                                       # q_b too large
+    assert call(Q.make_act(2, bad, 1 << 30, 45), f(4096), 1, 4, 16, 0, 0, f(1 << 20)) == -3
+    assert call(ok, f(4096), 0, 4, 16, 0, 0, f(1 << 20)) == -2
+    assert call(ok, f(4096), 1, 4, 0, 0, 0, f(1 << 20)) == -2
+    assert call(ok, f(4096), 2, 4, 16, 63, 0, f(1 << 20)) == -2                                # stride < item
+    assert call(Q.make_act(3, e, 1 << 30, 45), f(4096), 2, 4, 16, 64, 0, f(1 << 20)) == -2     # GLU item is 2 C T
+    assert call(ok, f(4096), 2, 4, 16, 0, 0, f(4096 + 32)) == -5                               # partial overlap
+    assert call(ok, f(4096), 2, 4, 16, 128, 64, f(4096)) == -5                                 # same base, other stride
+    sm = lambda c, x, rows, Lr, y: L.qasr_softmax_int32(ctypes.byref(c) if c is not None else None, x, rows, Lr, y, None)
+    assert sm(None, f(4096), 4, 16, f(1 << 20)) == -1
+    assert sm(e, None, 4, 16, f(1 << 20)) == -1
+    assert sm(e, f(4096), 0, 16, f(1 << 20)) == -2
+    assert sm(e, f(4096), 4, 0, f(1 << 20)) == -2
+    assert sm(e, f(4096), 4, 16385, f(1 << 20)) == -2
+    assert sm(Q.IExp(17, 0, 10, 10, 10), f(4096), 4, 16, f(1 << 20)) == -3
+    assert sm(e, f(4096), 4, 16, f(4096 + 100)) == -5
+
+
+def test_encoder_create_validates_activations_on_the_host():
+    e = Q.iexp_init(6.0 / 127, 8)
+    def create(act, Cout=4):
+        arr = (_Op * 1)()
+        arr[0] = _Op(make_desc(1, 4, Cout, 10), 4096, None, 4096, 4096, 0, -1, 1,
+                     ctypes.pointer(act) if act is not None else None)
+        h = ctypes.c_void_p()
+        st = Q.lib().qasr_encoder_create(arr, 1, 2, ctypes.byref(h))
+        assert not h.value or st == 0
+        return st
+    assert create(Q.make_act(7, e, 1 << 30, 45)) == -3
+    assert create(Q.make_act(Q.ACT_SWISH, e, 1 << 30, 99)) == -3
+    assert create(Q.make_act(Q.ACT_GLU, e, 1 << 30, 45), Cout=5) == -2          # GLU needs an even channel count
+
+
 def _ops(specs):
     arr = (_Op * len(specs))()
     for i, (d, i_s, r_s, o_s) in enumerate(specs):
-        arr[i] = _Op(d, 4096, None, 4096, 4096, i_s, r_s, o_s)
+        arr[i] = _Op(d, 4096, None, 4096, 4096, i_s, r_s, o_s, None)
     return arr
 
 

@@ -456,3 +456,92 @@ def test_dequantiser_matches_oracle(n, S, offset):
     got = xd.cpu().numpy()
     assert np.array_equal(got[offset:offset + n].view(np.uint32), ref.view(np.uint32))   # bit for bit
     assert np.all(got[:offset] == -7.0) and np.all(got[offset + n:] == -7.0)
+
+
+# ----------------------------------------------------------------------------- integer activations
+ACT_CASES = [
+    # kind, B, C, T, S, u, m, s, layout
+    (Q.ACT_SWISH, 2, 64, 400, 6.0 / 127, 8, 1 << 30, 45, "dense"),
+    (Q.ACT_SWISH, 16, 2048, 400, 5.1 / 127, 8, 1518500250, 45, "inplace"),       # ffn1 of configuration 4
+    (Q.ACT_SWISH, 3, 7, 37, 8.0 / 127, 6, 1300000000, 44, "dense"),               # ragged: element-wise tail
+    (Q.ACT_SWISH, 2, 5, 33, 4.0 / 127, 8, 1 << 30, 45, "unaligned"),
+    (Q.ACT_SWISH, 3, 16, 64, 4.4 / 127, 8, 2000000000, 46, "strided"),
+    (Q.ACT_SIGMOID, 2, 32, 100, 6.0 / 127, 8, 1 << 30, 38, "dense"),              # sigma at scale 2^-7
+    (Q.ACT_SIGMOID, 1, 1, 256, 16.0 / 127, 10, 1 << 30, 38, "all_codes"),
+    (Q.ACT_SWISH, 1, 1, 256, 0.1, 6, 1 << 30, 45, "all_codes"),
+    (Q.ACT_SWISH, 1, 1, 256, 6.0 / 127, 8, 123456789, 20, "all_codes"),           # small s: saturating outputs
+    (Q.ACT_GLU, 2, 64, 400, 6.0 / 127, 8, 1 << 30, 45, "dense"),
+    (Q.ACT_GLU, 16, 512, 400, 6.6 / 127, 8, 1700000000, 45, "inplace"),           # pw1 of configuration 4
+    (Q.ACT_GLU, 3, 7, 37, 8.0 / 127, 6, 1300000000, 44, "dense"),                 # halves off the 16-byte grid
+    (Q.ACT_GLU, 2, 5, 33, 4.0 / 127, 8, 1 << 30, 45, "unaligned"),
+    (Q.ACT_GLU, 3, 16, 64, 4.4 / 127, 8, 2000000000, 46, "strided"),
+    (Q.ACT_GLU, 1, 256, 256, 5.0 / 127, 8, 1 << 30, 45, "all_pairs"),
+]
+
+
+@pytest.mark.parametrize("kind,B,C,T,S,u,m,s,layout", ACT_CASES)
+def test_activations_match_oracle(kind, B, C, T, S, u, m, s, layout):
+    say(f"act kind={kind} B={B} C={C} T={T} S={S:.5f} u={u} m={m} s={s} {layout}")
+    Cx = 2 * C if kind == Q.ACT_GLU else C
+    x = randint_array(31 + C + T, (B, Cx, T), -128, 127, np.int8)
+    if layout == "all_codes":
+        x[0, 0, :] = np.arange(-128, 128)
+    if layout == "all_pairs":                      # value c - 128 against every gate code
+        x[0, :C] = (np.arange(C) - 128).reshape(C, 1)
+        x[0, C:] = (np.arange(T) - 128).reshape(1, T)
+    ref = oracle.act(kind, x, oracle.iexp_constants(S, u), m, s)
+    a = Q.make_act(kind, Q.iexp_init(S, u), m, s)
+    off = 1 if layout == "unaligned" else 0
+    xbs = Cx * T + (48 if layout == "strided" else 0)
+    ybs = xbs if layout == "inplace" else C * T + (80 if layout == "strided" else 0)
+    xd = torch.full((off + B * xbs + 8,), 55, dtype=torch.int8, device="cuda")
+    xd[off:off + B * xbs].view(B, xbs)[:, :Cx * T] = torch.from_numpy(x.reshape(B, -1)).cuda()
+    yd = xd if layout == "inplace" else torch.full((off + B * ybs + 8,), 99, dtype=torch.int8, device="cuda")
+    before = xd.clone()
+    Q.act_int8(a, xd[off:], B, C, T, yd[off:], xbs, ybs)
+    torch.cuda.synchronize()
+    got = yd.cpu().numpy()
+    body = got[off:off + B * ybs].reshape(B, ybs)
+    assert np.array_equal(body[:, :C * T].reshape(B, C, T), ref)
+    # nothing else written: the gaps between items, the bytes before and after, the gate half
+    fill = before.cpu().numpy() if layout == "inplace" else np.full_like(got, 99)
+    assert np.array_equal(body[:, C * T:], fill[off:off + B * ybs].reshape(B, ybs)[:, C * T:])
+    assert np.array_equal(got[:off], fill[:off]) and np.array_equal(got[off + B * ybs:], fill[off + B * ybs:])
+    if layout != "inplace":
+        assert torch.equal(xd, before)
+    if C * T >= 256 and s >= 38:
+        assert len(set(ref.reshape(-1).tolist())) > 16
+
+
+@pytest.mark.parametrize("rows,L,S,u", [(1, 1, 0.01, 2), (7, 37, 0.002, 0), (64, 400, 0.01, 2), (3, 1000, 1.0 / 64, 4),
+                                         (2, 16384, 0.004, 1), (1024, 400, 0.0073, 3)])
+def test_softmax_matches_oracle(rows, L, S, u):
+    say(f"softmax rows={rows} L={L} S={S} u={u}")
+    x = randint_array(41 + L, (rows, L), -int(6 / S), int(6 / S), np.int32)
+    x[0, :: max(1, L // 5)] = np.int32(2_000_000_000)          # int32 extremes must not wrap
+    if rows > 1:
+        x[1, :] = np.int32(-2_000_000_000)
+        x[1, L // 2] = np.int32(2_000_000_000)
+    ref = oracle.softmax(x, oracle.iexp_constants(S, u))
+    xd = torch.from_numpy(x).cuda()
+    yd = torch.full((rows * L + 16,), 99, dtype=torch.int8, device="cuda")
+    Q.softmax_int32(Q.iexp_init(S, u), xd, yd[: rows * L].view(rows, L))
+    torch.cuda.synchronize()
+    got = yd.cpu().numpy()
+    assert np.array_equal(got[: rows * L].reshape(rows, L), ref)
+    assert np.all(got[rows * L:] == 99)
+
+
+def test_tiny_conformer_with_integer_activations():
+    net = W.tiny_config(5)
+    params = W.draw_net_params(net, 3, s_lo=37, s_hi=38, bias_mag=300)
+    x = W.draw_input(net, 3)
+    g = GpuNet(net, params)
+    y = g.forward(dev(x)).cpu().numpy()
+    assert np.array_equal(y, oracle.encoder_forward(net, params, x))
+    g.enc.close()
+
+
+def test_conformer_shaped_batch16_with_integer_activations():
+    """Configuration 4 with Swish after ffn1 and the depthwise convolution and GLU after pw1."""
+    check_encoder(W.build_config(5), 1, items=[0, 15])
