@@ -63,6 +63,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time separate kernel launches instead of the HIP graph")
     ap.add_argument("--profile-passes", type=int, default=5, help="per-op timed passes for the roofline")
+    ap.add_argument("--softmax", default="", metavar="ROWS,LEN",
+                    help="also run 12 qasr_softmax_int32 calls on seeded int32 logits of this shape (for profiler runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the steps, run one plain elementwise int8 kernel that reads and writes this many MiB "
                          "(the known-size dispatch that calibrates the HBM byte counters of a --pmc run)")
@@ -119,6 +121,18 @@ def main():
     other_ms = None if args.eager else timed(lambda: enc.forward(x, y, ws), 3, max(5, args.steps // 5))[0]
     frames = net.B * net.Tin
     value = frames / (ms_per_step * 1e-3)
+
+    if args.softmax:
+        # a side measurement for profiler runs: the integer softmax on attention-shaped logits
+        rows_sm, len_sm = (int(v) for v in args.softmax.split(","))
+        from qasr_workloads.rng import randint_array
+        lg = torch.from_numpy(randint_array(args.seed, (rows_sm, len_sm), -600, 600, np.int32)).cuda()
+        pr = torch.empty((rows_sm, len_sm), dtype=torch.int8, device="cuda")
+        e_sm = Q.iexp_init(0.01, 2)
+        for _ in range(12):
+            Q.softmax_int32(e_sm, lg, pr)
+        torch.cuda.synchronize()
+        del lg, pr
 
     if args.calib_copy_mib > 0:
         a = torch.zeros(args.calib_copy_mib << 20, dtype=torch.int8, device="cuda")

@@ -177,8 +177,9 @@ qasr_status qasr_act_int8(const qasr_act* a, const int8_t* x, int32_t B, int32_t
 /* Softmax over the last axis of int32 logits at the scale of `e` (attention scores):
  *   r_i = (q_i - max_j q_j) 2^u,  E_i = iexp(r_i),  y_i = min(127, floor(E_i 2^7 / sum_j E_j)),
  * probabilities at scale 2^-7.  x: [rows, L] int32 device, y: [rows, L] int8 device, dense;
- * 1 <= L <= 16384 (the 64-bit sum cannot overflow), rows >= 1, else QASR_ERR_SHAPE; y must not
- * overlap x.  Enqueues one kernel on `stream` and returns. */
+ * 1 <= L <= 16384, rows >= 1, else QASR_ERR_SHAPE; L (q_b^2 + q_c) < 2^55 (the 64-bit row sum
+ * cannot overflow), else QASR_ERR_PARAM; y must not overlap x.  Enqueues one kernel on `stream`
+ * and returns. */
 qasr_status qasr_softmax_int32(const qasr_iexp* e, const int32_t* x, int64_t rows, int32_t L,
                                int8_t* y, void* stream);
 

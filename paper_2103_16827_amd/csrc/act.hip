@@ -17,8 +17,12 @@
 // tensor through it, 16 bytes per lane and access.  The pass is memory-bound (2 bytes per element,
 // 3 for GLU); the table costs each workgroup a few hundred cycles once.
 //
-// Softmax: one workgroup per row, three passes over the row (maximum, sum of exponentials,
-// quotients) with 64-bit integer arithmetic per element; the row stays in cache between passes.
+// Softmax: one wave per row up to 512 logits (no barrier, the row in registers), one workgroup per
+// row beyond: extremes of the row, exponentials (kept in registers for rows up
+// to 2048 logits, recomputed beyond) and their 64-bit sum, quotients.  The two divisions per
+// element are 32-bit whenever the row's spread allows it (the choice is made per row and is
+// wave-uniform): floor(-r / q_ln2) directly, and E 2^7 / sum through a 24-bit cut of both operands
+// whose quotient the exact 64-bit remainder corrects by at most one.
 #include "kernels.hpp"
 
 namespace qasr {
@@ -116,8 +120,8 @@ __global__ __launch_bounds__(256) void act_glu_kernel(ActParams c, const int8_t*
     yb[i] = (int8_t)rescale_clamp((int32_t)xa[i] * (int32_t)lut[(uint8_t)xg[i] ^ 0x80u], m, s);
 }
 
-__device__ __forceinline__ long long wg_reduce(long long v, bool is_max, long long* sh) {
-  // 256 threads: butterfly inside each wave, then the four wave results through LDS
+// butterfly over the 64 lanes of a wave: every lane ends with the maximum / the sum
+__device__ __forceinline__ long long wave_reduce(long long v, bool is_max) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) {
     const int lo = __shfl_xor((int)(uint32_t)(unsigned long long)v, o);
@@ -125,11 +129,99 @@ __device__ __forceinline__ long long wg_reduce(long long v, bool is_max, long lo
     const long long w = (long long)(((unsigned long long)(uint32_t)hi << 32) | (uint32_t)lo);
     v = is_max ? (w > v ? w : v) : v + w;
   }
+  return v;
+}
+
+__device__ __forceinline__ long long wg_reduce(long long v, bool is_max, long long* sh) {
+  // 256 threads: inside each wave first, then the four wave results through LDS
+  v = wave_reduce(v, is_max);
   __syncthreads();                                   // sh may still be read from the previous use
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
   __syncthreads();
   const long long a = sh[0], b = sh[1], c = sh[2], d = sh[3];
   return is_max ? max(max(a, b), max(c, d)) : a + b + c + d;
+}
+
+// floor(n / d) for n < 2^31, 1 <= d < 2^30, when only quotients up to 63 matter (larger ones may come
+// out as any value above 62): one multiplication by the reciprocal (single precision: the
+// estimate is within one of the quotient while that is below 2^7), then the exact remainder
+// decides.  rcp_d = 1.0f / (float)d.
+__device__ __forceinline__ uint32_t div_small(uint32_t n, uint32_t d, float rcp_d, uint32_t& rem) {
+  const float e = (float)n * rcp_d;
+  uint32_t q = e >= 100.0f ? 100u : (uint32_t)e;               // only "> 62" matters up there
+  int32_t r = (int32_t)(n - q * d);                             // q d <= 100 d and <= n (1 + 2^-22): no wrap that matters below 63
+  if (q < 100u) {
+    if (r < 0) { --q; r += (int32_t)d; }
+    else if ((uint32_t)r >= d) { ++q; r -= (int32_t)d; }
+  }
+  rem = (uint32_t)r;
+  return q;
+}
+
+// exp of r <= 0 when -r < 2^31 and q_ln2 < 2^30 (FAST, wave-uniform choice made per row), else the
+// general form
+template <bool FAST>
+__device__ __forceinline__ long long iexp_row(long long r, const ActParams& c, float rcp_ql) {
+  if (!FAST) return iexp_dev(r, c);
+  const uint32_t nr = (uint32_t)(-r), ql = (uint32_t)c.q_ln2;
+  uint32_t rem;
+  const uint32_t z = div_small(nr, ql, rcp_ql, rem);
+  const long long tp = (long long)((int32_t)(uint32_t)c.q_b - (int32_t)rem);      // p + q_b, p = -rem
+  const long long L = tp * tp + c.q_c;
+  return z > 62 ? 0 : (L >> z);
+}
+
+// floor(a / b) for 0 <= a <= 128 b, 1 <= b < 2^55: both operands are cut to b's leading 24 bits
+// (shift sh, b1 = b >> sh, rcp_b1 = 1.0f / (float)b1); the single-precision quotient of the cuts is
+// within one of the true one (the cuts move a/b by less than 2^-15, the arithmetic by less than
+// 2^-14), and the exact 64-bit remainder decides.
+__device__ __forceinline__ uint32_t div_small_quotient(unsigned long long a, unsigned long long b, int sh, float rcp_b1) {
+  const uint32_t a1 = (uint32_t)(a >> sh);
+  uint32_t q = (uint32_t)((float)a1 * rcp_b1);
+  const long long rem = (long long)a - (long long)((unsigned long long)q * b);
+  if (rem < 0) --q;
+  else if ((unsigned long long)rem >= b) ++q;
+  return q;
+}
+
+template <bool FAST>
+__device__ __forceinline__ void softmax_row(const ActParams& c, const int32_t* __restrict__ xr, int32_t L,
+                                            int8_t* __restrict__ yr, long long mx, long long* sh) {
+  constexpr int K = 8;                               // elements per thread kept in registers
+  const long long mul = 1ll << c.u;
+  const float rcp_ql = 1.0f / (float)(uint32_t)(c.q_ln2 < (1ll << 30) ? c.q_ln2 : 1);
+  if (L <= 256 * K) {
+    long long E[K];
+    long long sum = 0;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const int j = threadIdx.x + 256 * k;
+      E[k] = j < L ? iexp_row<FAST>(((long long)xr[j] - mx) * mul, c, rcp_ql) : 0;
+      sum += E[k];
+    }
+    sum = wg_reduce(sum, false, sh);
+    const int shn = max(0, 40 - __clzll(sum));       // sum >> shn has at most 24 bits
+    const float rcp_b1 = 1.0f / (float)(uint32_t)((unsigned long long)sum >> shn);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const int j = threadIdx.x + 256 * k;
+      if (j < L) {
+        const uint32_t p = div_small_quotient((unsigned long long)E[k] << 7, (unsigned long long)sum, shn, rcp_b1);
+        yr[j] = (int8_t)(p > 127 ? 127 : p);
+      }
+    }
+  } else {
+    long long sum = 0;
+    for (int j = threadIdx.x; j < L; j += 256) sum += iexp_row<FAST>(((long long)xr[j] - mx) * mul, c, rcp_ql);
+    sum = wg_reduce(sum, false, sh);
+    const int shn = max(0, 40 - __clzll(sum));
+    const float rcp_b1 = 1.0f / (float)(uint32_t)((unsigned long long)sum >> shn);
+    for (int j = threadIdx.x; j < L; j += 256) {
+      const unsigned long long E = (unsigned long long)iexp_row<FAST>(((long long)xr[j] - mx) * mul, c, rcp_ql);
+      const uint32_t p = div_small_quotient(E << 7, (unsigned long long)sum, shn, rcp_b1);
+      yr[j] = (int8_t)(p > 127 ? 127 : p);
+    }
+  }
 }
 
 __global__ __launch_bounds__(256) void softmax_kernel(ActParams c, const int32_t* __restrict__ x, int64_t rows, int32_t L,
@@ -138,17 +230,68 @@ __global__ __launch_bounds__(256) void softmax_kernel(ActParams c, const int32_t
   for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
     const int32_t* xr = x + row * L;
     int8_t* yr = y + row * L;
-    long long mx = INT32_MIN;
-    for (int j = threadIdx.x; j < L; j += 256) mx = max(mx, (long long)xr[j]);
-    mx = wg_reduce(mx, true, sh);
-    long long sum = 0;
-    for (int j = threadIdx.x; j < L; j += 256) sum += iexp_dev(((long long)xr[j] - mx) * (1ll << c.u), c);
-    sum = wg_reduce(sum, false, sh);
+    long long mx = INT32_MIN, mn = INT32_MAX;
     for (int j = threadIdx.x; j < L; j += 256) {
-      const unsigned long long E = (unsigned long long)iexp_dev(((long long)xr[j] - mx) * (1ll << c.u), c);
-      const unsigned long long p = (E << 7) / (unsigned long long)sum;      // sum >= E0 > 0 (the maximum's own term)
-      yr[j] = (int8_t)(p > 127 ? 127 : p);
+      const long long v = xr[j];
+      mx = max(mx, v);
+      mn = min(mn, v);
     }
+    mx = wg_reduce(mx, true, sh);
+    mn = -wg_reduce(-mn, true, sh);
+    // every (max - q) 2^u of the row below 2^31, and the constants too: 32-bit exponentials
+    const bool fast = ((mx - mn) << c.u) < (1ll << 31) && c.q_ln2 < (1ll << 30);
+    if (fast) softmax_row<true>(c, xr, L, yr, mx, sh);
+    else softmax_row<false>(c, xr, L, yr, mx, sh);
+  }
+}
+
+// Rows of up to 512 logits: one wave per row (no barrier, the row lives in registers: 8 logits per
+// lane), four rows per workgroup.
+template <bool FAST>
+__device__ __forceinline__ void softmax_wave_row(const ActParams& c, const int32_t (&xv)[8], int32_t L, int lane,
+                                                 int8_t* __restrict__ yr, long long mx) {
+  const long long mul = 1ll << c.u;
+  const float rcp_ql = 1.0f / (float)(uint32_t)(c.q_ln2 < (1ll << 30) ? c.q_ln2 : 1);
+  long long E[8];
+  long long sum = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) {
+    E[k] = lane + 64 * k < L ? iexp_row<FAST>(((long long)xv[k] - mx) * mul, c, rcp_ql) : 0;
+    sum += E[k];
+  }
+  sum = wave_reduce(sum, false);
+  const int shn = max(0, 40 - __clzll(sum));
+  const float rcp_b1 = 1.0f / (float)(uint32_t)((unsigned long long)sum >> shn);
+#pragma unroll
+  for (int k = 0; k < 8; ++k)
+    if (lane + 64 * k < L) {
+      const uint32_t p = div_small_quotient((unsigned long long)E[k] << 7, (unsigned long long)sum, shn, rcp_b1);
+      yr[lane + 64 * k] = (int8_t)(p > 127 ? 127 : p);
+    }
+}
+
+__global__ __launch_bounds__(256) void softmax_wave_kernel(ActParams c, const int32_t* __restrict__ x, int64_t rows,
+                                                           int32_t L, int8_t* __restrict__ y) {
+  const int lane = threadIdx.x & 63;
+  const int64_t nw = (int64_t)gridDim.x * 4;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < rows; row += nw) {
+    const int32_t* xr = x + row * L;
+    int32_t xv[8];
+    long long mx = INT32_MIN, mn = INT32_MAX;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const bool in = lane + 64 * k < L;
+      xv[k] = in ? xr[lane + 64 * k] : 0;
+      if (in) {
+        mx = max(mx, (long long)xv[k]);
+        mn = min(mn, (long long)xv[k]);
+      }
+    }
+    mx = wave_reduce(mx, true);
+    mn = -wave_reduce(-mn, true);
+    const bool fast = ((mx - mn) << c.u) < (1ll << 31) && c.q_ln2 < (1ll << 30);      // wave-uniform
+    if (fast) softmax_wave_row<true>(c, xv, L, lane, y + row * L, mx);
+    else softmax_wave_row<false>(c, xv, L, lane, y + row * L, mx);
   }
 }
 
@@ -170,6 +313,10 @@ hipError_t launch_act(const ActParams& c, const int8_t* x, int8_t* y, int32_t B,
 }
 
 hipError_t launch_softmax(const ActParams& c, const int32_t* x, int64_t rows, int32_t L, int8_t* y, hipStream_t st) {
+  if (L <= 512) {
+    const int64_t wgs = (rows + 3) / 4;
+    return launch_kernel(softmax_wave_kernel, dim3((unsigned)(wgs < 16384 ? wgs : 16384)), dim3(256), 0, st, c, x, rows, L, y);
+  }
   const unsigned grid = (unsigned)(rows < 8192 ? rows : 8192);
   return launch_kernel(softmax_kernel, dim3(grid), dim3(256), 0, st, c, x, rows, L, y);
 }

@@ -273,6 +273,8 @@ qasr_status qasr_softmax_int32(const qasr_iexp* e, const int32_t* x, int64_t row
   if (st != QASR_OK) return st;
   if (!x || !y) return QASR_ERR_NULL;
   if (rows < 1 || L < 1 || L > 16384 || rows > ((int64_t)1 << 40) / L) return QASR_ERR_SHAPE;
+  // the row sum of exponentials (each at most q_b^2 + q_c) times 2^8 must stay inside 64 bits
+  if ((double)L * ((double)e->q_b * (double)e->q_b + (double)e->q_c) >= 36028797018963968.0) return QASR_ERR_PARAM;
   if (overlaps(y, rows * L, x, 4 * rows * L)) return QASR_ERR_ALIAS;
   return hip_status(qasr::launch_softmax(act_params(0, 0, 1, *e), x, rows, L, y, (hipStream_t)stream));
 }

@@ -136,6 +136,7 @@ def test_activation_arguments_rejected_before_any_launch():
     assert sm(e, f(4096), 4, 16385, f(1 << 20)) == -2
     assert sm(Q.IExp(17, 0, 10, 10, 10), f(4096), 4, 16, f(1 << 20)) == -3
     assert sm(e, f(4096), 4, 16, f(4096 + 100)) == -5
+    assert sm(Q.IExp(0, 0, 1 << 22, (1 << 24) - 1, 1 << 47), f(4096), 4, 16384, f(1 << 20)) == -3   # row sum could overflow
 
 
 def test_encoder_create_validates_activations_on_the_host():
