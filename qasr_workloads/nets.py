@@ -147,10 +147,16 @@ def separable_module(B=1, C=256, T=200, k=33, config_id=0) -> NetSpec:
 
 
 def quartznet(B, T, repeat, config_id, Cin=64, widths=(256, 256, 512, 512, 512),
-              kernels=(33, 39, 51, 63, 75), k1=33, k2=87, C3=1024, n_out=29, name=None) -> NetSpec:
-    """QuartzNet-(5*repeat)x5-shaped encoder (configs 1 and 2)."""
+              kernels=(33, 39, 51, 63, 75), k1=33, k2=87, C3=1024, n_out=29, name=None,
+              separable_c1=False) -> NetSpec:
+    """QuartzNet-(5*repeat)x5-shaped encoder (configs 1 and 2; repeat = 2 is the 10x5 variant).
+    `separable_c1` makes the stride-2 first layer a depthwise + pointwise pair like the others."""
     b = _Builder(name or f"quartznet_{5 * repeat}x5", config_id, B, Cin, T)
-    b.op("C1", widths[0], k=k1, stride=2, pad=((k1 - 1) // 2, (k1 - 1) // 2))
+    if separable_c1:
+        b.op("C1.dw", Cin, k=k1, stride=2, pad=((k1 - 1) // 2, (k1 - 1) // 2), groups=Cin, relu=False, bias=False)
+        b.op("C1.pw", widths[0])
+    else:
+        b.op("C1", widths[0], k=k1, stride=2, pad=((k1 - 1) // 2, (k1 - 1) // 2))
     for bi, (W, k) in enumerate(zip(widths, kernels)):
         for r in range(repeat):
             tag = f"B{bi + 1}.{r}"
@@ -235,6 +241,9 @@ def tiny_config(i: int) -> NetSpec:
     if i == 5:
         return conformer_shaped(2, 9, config_id=105, d_model=4, d_ff=8, k=4, layers=2,
                                 name="tiny_conformer_nonlinear", nonlinear=True)
+    if i == 6:
+        return quartznet(2, 24, 1, config_id=106, Cin=3, widths=(4, 4, 8, 8, 8), kernels=(3, 5, 3, 5, 7),
+                         k1=5, k2=5, C3=6, n_out=3, name="tiny_quartznet_separable_c1", separable_c1=True)
     raise ValueError(i)
 
 
@@ -247,20 +256,22 @@ def net_weight_count(net: NetSpec) -> int:
 
 
 def draw_net_params(net: NetSpec, seed: int, m_lo=1 << 30, m_hi=(1 << 31) - 1, s_lo=36, s_hi=44,
-                    bias_mag=1 << 16):
+                    bias_mag=1 << 16, w_bits=8):
     """Per-op constants as the offline quantiser would emit them (here: seeded draws).
 
-    w int8 U[-127,127] in PyTorch Conv1d order [Cout, Cin/groups, k]; bias int32
+    w int8 U[-(2^(w_bits-1) - 1), 2^(w_bits-1) - 1] (w_bits = 6: the W6A8 setting, 6-bit codes in int8
+    storage) in PyTorch Conv1d order [Cout, Cin/groups, k]; bias int32
     U[-bias_mag, bias_mag] (default 2^16) or None; m int32 U[2^30, 2^31); s int32 U{36..44}.
     An op with an activation also gets "act": the real scale S of its int8 input (U[4, 8] / 127 in
     steps of 0.01 / 127), the refinement shift u = 8, and the activation's own output rescale
     (m U[2^30, 2^31), s = 45: a ratio in [2^-15, 2^-14), i.e. about the input's own scale)."""
     out = []
+    wmax = (1 << (w_bits - 1)) - 1
     for i, o in enumerate(net.ops):
         cin_g = 1 if o.depthwise else o.Cin
         sd = lambda kind: tensor_seed(seed, net.config_id, i, kind)
         p = {
-            "w": randint_array(sd("w"), (o.Cout, cin_g, o.k), -127, 127, np.int8),
+            "w": randint_array(sd("w"), (o.Cout, cin_g, o.k), -wmax, wmax, np.int8),
             "bias": randint_array(sd("bias"), (o.Cout,), -bias_mag, bias_mag, np.int32) if o.has_bias else None,
             "m": randint_array(sd("m"), (o.Cout,), m_lo, m_hi, np.int32),
             "s": randint_array(sd("s"), (o.Cout,), s_lo, s_hi, np.int32),

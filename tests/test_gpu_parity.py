@@ -275,10 +275,10 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
 
 
 # ----------------------------------------------------------------------------- encoders
-def check_encoder(net, seed, items=None):
+def check_encoder(net, seed, items=None, **draw_kw):
     """GPU forward of the whole batch vs the oracle on the chosen batch items (each item of the
     batch is an independent utterance, so its output equals the oracle run on that item alone)."""
-    params = W.draw_net_params(net, seed)
+    params = W.draw_net_params(net, seed, **draw_kw)
     x = W.draw_input(net, seed)
     g = GpuNet(net, params)
     y = g.forward(dev(x)).cpu().numpy()
@@ -545,3 +545,22 @@ def test_tiny_conformer_with_integer_activations():
 def test_conformer_shaped_batch16_with_integer_activations():
     """Configuration 4 with Swish after ffn1 and the depthwise convolution and GLU after pw1."""
     check_encoder(W.build_config(5), 1, items=[0, 15])
+
+
+# ----------------------------------------------------------------------------- variants of the same families
+def test_quartznet_10x5():
+    """The medium model of the latency comparison (Sec. 3.2): each block type twice."""
+    check_encoder(W.quartznet(4, 1600, 2, config_id=6), 1, items=[0, 3])
+
+
+def test_quartznet_15x5_with_separable_first_layer():
+    net = W.quartznet(2, 1600, 3, config_id=7, separable_c1=True)
+    check_encoder(net, 1, items=[1])
+
+
+@pytest.mark.parametrize("cfg", [1, 3])
+def test_w6a8_six_bit_weight_codes_in_int8_storage(cfg):
+    """W6A8 (Sec. 3.1): weights in [-31, 31]; the rescale shifts are two smaller so that the
+    activations keep their range."""
+    net = W.build_config(1) if cfg == 1 else W.jasper(2, 400, config_id=3)
+    check_encoder(net, 2, w_bits=6, s_lo=34, s_hi=42)

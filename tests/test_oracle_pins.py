@@ -287,12 +287,13 @@ def py_encoder(net, params, x):
     return slots[net.ops[-1].out_slot]
 
 
-@pytest.mark.parametrize("cfg", range(5))
-def test_tiny_encoders_match_big_int_composition(cfg):
+@pytest.mark.parametrize("cfg,w_bits", [(0, 8), (1, 8), (2, 8), (3, 8), (4, 8), (6, 8), (1, 6)])
+def test_tiny_encoders_match_big_int_composition(cfg, w_bits):
     net = W.tiny_config(cfg)
     for seed in (1, 2):
         # scales chosen for the tiny fan-in so that layers neither saturate nor vanish
-        params = W.draw_net_params(net, seed, s_lo=37, s_hi=38, bias_mag=300)
+        params = W.draw_net_params(net, seed, s_lo=37 - (8 - w_bits), s_hi=38 - (8 - w_bits), bias_mag=300,
+                                   w_bits=w_bits)
         x = W.draw_input(net, seed)
         y, outs = oracle.encoder_forward(net, params, x, keep=True)
         assert y.tolist() == py_encoder(net, params, x)

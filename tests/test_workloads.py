@@ -68,6 +68,28 @@ def test_networks_agree_with_paper_table1_size_and_bops(golden):
         assert W.net_macs(net) * 64 / 1e12 == pytest.approx(bops_t, rel=0.10)
 
 
+def test_variants_of_the_same_families():
+    """QuartzNet-10x5 (the medium model of Sec. 3.2), the separable first layer, 6-bit weights."""
+    q10 = W.quartznet(1, 1600, 2, config_id=6)
+    assert q10.name == "quartznet_10x5" and len(q10.ops) == 1 + 10 * 11 + 4
+    assert sum(o.depthwise for o in q10.ops) == 51 and (q10.Cout, q10.Tout) == (29, 800)
+    q5, q15 = W.build_config(1), W.quartznet(1, 1600, 3, config_id=2)
+    # weights grow by one repeat of the five block types per step
+    assert W.net_weight_count(q15) - W.net_weight_count(q10) == W.net_weight_count(q10) - W.net_weight_count(q5)
+    # a separable first layer brings the 15x5 shape to within 2.5 % of the paper's model size
+    qs = W.quartznet(1, 1000, 3, config_id=2, separable_c1=True)
+    assert [o.name for o in qs.ops[:3]] == ["C1.dw", "C1.pw", "B1.0.res"]
+    assert (qs.ops[0].groups, qs.ops[0].stride, qs.ops[0].Tout, qs.ops[1].Cin, qs.ops[1].Cout) == (64, 2, 500, 64, 256)
+    assert W.net_weight_count(qs) / 1e6 == pytest.approx(18.45, rel=0.025)
+    # W6A8: 6-bit codes [-31, 31] in int8 storage, everything else unchanged
+    p8, p6 = W.draw_net_params(q5, 1), W.draw_net_params(q5, 1, w_bits=6)
+    for a, b in zip(p8, p6):
+        assert b["w"].dtype == np.int8 and b["w"].min() >= -31 and b["w"].max() <= 31
+        assert np.array_equal(a["m"], b["m"]) and np.array_equal(a["s"], b["s"])
+    big = p6[2]["w"]
+    assert big.min() == -31 and big.max() == 31 and len(set(big.reshape(-1).tolist())) == 63
+
+
 @pytest.mark.parametrize("cfg", range(5))
 def test_slot_wiring_is_hazard_free(cfg):
     """No op writes a slot it reads, slot 0 is never written, and every read slot holds the
