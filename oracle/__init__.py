@@ -43,6 +43,9 @@ def lib():
         L.qasr_oracle_conv1d_int8.restype = i64
         L.qasr_oracle_conv1d_int8.argtypes = [i32, i32, i32, i64, i32, i32, i32, i32, i32, i32, i64, i64, u32,
                                               p, p, p, p, p, p, p]
+        L.qasr_oracle_conv1d_int8_multi.restype = i64
+        L.qasr_oracle_conv1d_int8_multi.argtypes = [i32, i32, i32, i64, i32, i32, i32, i32, i32, i32, i64, i64, u32,
+                                                    p, p, p, p, p, p, i32, p]
         L.qasr_oracle_requant.restype = None
         L.qasr_oracle_requant.argtypes = [p, i32, i32, i64, p, p, p, p, u32, p]
         L.qasr_oracle_requant_scalar.restype = i64
@@ -105,6 +108,18 @@ def conv1d_int8(x, w, bias, m, s, residual=None, *, stride=1, dilation=1, pad_le
     Cout, _, k = w.shape
     Tout = out_len(Tin, k, stride, dilation, pad_left, pad_right)
     y = np.empty((B, Cout, Tout), dtype=np.int8)
+    if isinstance(residual, (list, tuple)):          # several residual operands: summed, one clamp
+        rs = [np.ascontiguousarray(r, dtype=np.int8) for r in residual]
+        assert all(r.shape == y.shape for r in rs)
+        arr = (ctypes.c_void_p * len(rs))(*[r.ctypes.data for r in rs])
+        ovf = lib().qasr_oracle_conv1d_int8_multi(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right,
+                                                  groups, x_batch_stride, 0, 1 if relu else 0,
+                                                  _ptr(x, np.int8), _ptr(w, np.int8), _ptr(bias, np.int32),
+                                                  _ptr(m, np.int32), _ptr(s, np.int32), arr, len(rs),
+                                                  _ptr(y, np.int8))
+        if check_overflow and ovf:
+            raise OverflowError(f"{ovf} accumulators left the int32 range")
+        return y
     if residual is not None:
         assert residual.shape == y.shape
     ovf = lib().qasr_oracle_conv1d_int8(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right, groups,
@@ -214,6 +229,8 @@ def encoder_forward(net, params, x, keep=False):
     for op, p in zip(net.ops, params):
         xin = slots[op.in_slot]
         res = slots[op.res_slot] if op.res_slot >= 0 else None
+        if getattr(op, "more_res", None):
+            res = [res] + [slots[r] for r in op.more_res]
         y = run_op(op, p, xin, res)
         if getattr(op, "act", 0):
             y = apply_act(p["act"], y)

@@ -139,6 +139,38 @@ int64_t qasr_oracle_conv1d_int8(int B, int Cin, int Cout, int64_t Tin, int k, in
     return overflow;
 }
 
+// The same layer with several residual operands (the dense-residual wiring of the Jasper family
+// named in Sec. 3: a block receives the projected inputs of all earlier blocks).  The paper does
+// not say how the operands combine in integers; the reading: every operand is int8 at the output
+// scale, all are added to the unsaturated requantised value, one clamp follows:
+//     v = requant(A) + sum_r residual_r ;  y = clamp(v)
+// (n_res = 1 is the layer above; saturating after each addition would differ, a pin separates them).
+int64_t qasr_oracle_conv1d_int8_multi(int B, int Cin, int Cout, int64_t Tin, int k, int stride, int dil,
+                                      int pl, int pr, int groups, int64_t x_batch_stride,
+                                      int64_t y_batch_stride, uint32_t flags,
+                                      const int8_t* x, const int8_t* w, const int32_t* bias,
+                                      const int32_t* m, const int32_t* s,
+                                      const int8_t* const* residuals, int n_res, int8_t* y) {
+    const int64_t Tout = out_len(Tin, k, stride, dil, pl, pr);
+    const bool dw = groups != 1;
+    const bool relu = (flags & 1u) != 0;
+    const int64_t xbs = x_batch_stride ? x_batch_stride : int64_t(Cin) * Tin;
+    const int64_t ybs = y_batch_stride ? y_batch_stride : int64_t(Cout) * Tout;
+    int64_t overflow = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(+ : overflow)
+    for (int b = 0; b < B; ++b)
+        for (int co = 0; co < Cout; ++co)
+            for (int64_t to = 0; to < Tout; ++to) {
+                const int64_t A = acc_one(x + b * xbs, w, bias, Cin, Tin, k, stride, dil, pl, dw, co, to);
+                if (A < INT32_MIN || A > INT32_MAX) ++overflow;
+                int64_t v = requant_one(A, m[co], s[co]);
+                const int64_t o = b * ybs + int64_t(co) * Tout + to;
+                for (int r = 0; r < n_res; ++r) v += int64_t(residuals[r][o]);
+                y[o] = clamp_out(v, relu);
+            }
+    return overflow;
+}
+
 // Standalone epilogue: A = acc + bias, then exactly the last four steps above.
 void qasr_oracle_requant(const int32_t* acc, int B, int C, int64_t T, const int32_t* bias,
                          const int32_t* m, const int32_t* s, const int8_t* residual,

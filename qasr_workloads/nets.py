@@ -42,6 +42,7 @@ class OpSpec:
     res_slot: int = -1
     out_slot: int = 1
     act: int = 0                 # 0 none, 1 sigmoid, 2 swish, 3 GLU (applied in place to the output)
+    more_res: List[int] = field(default_factory=list)   # further residual operands (slots), summed with res_slot's
 
     @property
     def Tout(self) -> int:
@@ -92,16 +93,17 @@ class _Builder:
         self.n_tensors = 1
 
     def op(self, name, Cout, k=1, stride=1, dilation=1, pad=None, groups=1, relu=True,
-           bias=True, res=-1, Cin=None, x_batch_stride=0, advance=True, act=0):
+           bias=True, res=-1, Cin=None, x_batch_stride=0, advance=True, act=0, src=None, more_res=()):
         """Append one op reading the running activation; returns its output tensor id."""
-        Cin = self.C if Cin is None else Cin
+        cur = self.cur if src is None else src[0]      # src = (tensor id, channels): read another tensor
+        Cin = (self.C if src is None else src[1]) if Cin is None else Cin
         if pad is None:
             tot = dilation * (k - 1)
             pad = (tot // 2, tot - tot // 2)
         out = self.n_tensors
         self.n_tensors += 1
         o = OpSpec(name, Cin, Cout, self.T, k, stride, dilation, pad[0], pad[1], groups,
-                   x_batch_stride, FLAG_RELU if relu else 0, bias, self.cur, res, out, act)
+                   x_batch_stride, FLAG_RELU if relu else 0, bias, cur, res, out, act, list(more_res))
         self.net.ops.append(o)
         if advance:
             self.cur, self.C, self.T = out, Cout, o.Tout
@@ -115,6 +117,8 @@ class _Builder:
             last_use[o.in_slot] = i
             if o.res_slot >= 0:
                 last_use[o.res_slot] = i
+            for t in o.more_res:
+                last_use[t] = i
         slot_of, free, n = {0: 0}, [], 1
         for i, o in enumerate(ops):
             tin, tres, tout = o.in_slot, o.res_slot, o.out_slot
@@ -125,7 +129,9 @@ class _Builder:
             slot_of[tout] = s
             o.in_slot, o.out_slot = slot_of[tin], s
             o.res_slot = slot_of[tres] if tres >= 0 else -1
-            for t in {tin, tres}:
+            tmore = list(o.more_res)
+            o.more_res = [slot_of[t] for t in tmore]
+            for t in {tin, tres, *tmore}:
                 if t > 0 and last_use.get(t) == i:
                     free.append(slot_of[t])
             free.sort()
@@ -171,16 +177,28 @@ def quartznet(B, T, repeat, config_id, Cin=64, widths=(256, 256, 512, 512, 512),
 
 
 def jasper(B, T, config_id, Cin=64, widths=(256, 384, 512, 640, 768), kernels=(11, 13, 17, 21, 25),
-           per_width=2, k_pro=11, C_epi=896, k_epi=29, C_epi2=1024, n_out=29, name="jasper_10x5") -> NetSpec:
-    """Jasper-10x5-shaped dense stack (config 3): one residual per block from the block input."""
+           per_width=2, k_pro=11, C_epi=896, k_epi=29, C_epi2=1024, n_out=29, name="jasper_10x5",
+           dense_residual=False) -> NetSpec:
+    """Jasper-10x5-shaped dense stack (config 3): one residual per block from the block input.
+    With `dense_residual` (the DR variant the paper evaluates) a block receives, besides the
+    projection of its own input, the projections of the inputs of all earlier blocks: one
+    pointwise conv (bias, own scale, no ReLU) per earlier input, all added in the epilogue of the
+    block's last conv."""
     b = _Builder(name, config_id, B, Cin, T)
     b.op("prologue", widths[0], k=k_pro, stride=2, pad=((k_pro - 1) // 2, (k_pro - 1) // 2))
+    inputs = []                                   # (tensor id, channels) of every block input so far
     for wi, (W, k) in enumerate(zip(widths, kernels)):
         for r in range(per_width):
             tag = f"J{wi + 1}.{r}"
+            more = []
+            if dense_residual:
+                more = [b.op(f"{tag}.res_from{j}", W, relu=False, advance=False, src=src)
+                        for j, src in enumerate(inputs)]
+                inputs.append((b.cur, b.C))
             res = b.op(f"{tag}.res", W, relu=False, advance=False)
             for ci in range(5):
-                b.op(f"{tag}.c{ci}", W, k=k, relu=True, res=res if ci == 4 else -1)
+                b.op(f"{tag}.c{ci}", W, k=k, relu=True, res=res if ci == 4 else -1,
+                     more_res=more if ci == 4 else ())
     b.op("epilogue0", C_epi, k=k_epi, dilation=2)
     b.op("epilogue1", C_epi2)
     b.op("epilogue2", n_out, relu=False)
@@ -241,6 +259,10 @@ def tiny_config(i: int) -> NetSpec:
     if i == 5:
         return conformer_shaped(2, 9, config_id=105, d_model=4, d_ff=8, k=4, layers=2,
                                 name="tiny_conformer_nonlinear", nonlinear=True)
+    if i == 7:
+        return jasper(2, 20, config_id=107, Cin=3, widths=(4, 6, 5), kernels=(3, 5, 3), per_width=1,
+                      k_pro=3, C_epi=5, k_epi=3, C_epi2=6, n_out=3, name="tiny_jasper_dense_residual",
+                      dense_residual=True)
     if i == 6:
         return quartznet(2, 24, 1, config_id=106, Cin=3, widths=(4, 4, 8, 8, 8), kernels=(3, 5, 3, 5, 7),
                          k1=5, k2=5, C3=6, n_out=3, name="tiny_quartznet_separable_c1", separable_c1=True)

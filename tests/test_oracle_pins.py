@@ -49,7 +49,9 @@ def py_layer(x, w, bias, m, s, residual, stride, dil, pl, pr, depthwise, relu, C
                     A += sum(int(taps[j]) * padded[ci][start + j * dil] for j in range(k))
                 v = py_round_half_up(Fraction(A * int(m[co]), 2 ** int(s[co])))
                 if residual is not None:
-                    v += int(residual[b][co][to])
+                    # one operand [B][C][T], or a list of such operands: all added, one clamp
+                    ops_r = residual if isinstance(residual, tuple) else (residual,)
+                    v += sum(int(r[b][co][to]) for r in ops_r)
                 row.append(min(127, max(0 if relu else -128, v)))
                 to += 1
             yb.append(row)
@@ -275,11 +277,40 @@ def test_overflow_is_detected():
         oracle.conv1d_int8(x, w, None, m, s)
 
 
+def test_several_residual_operands_are_summed_before_the_one_clamp():
+    """Dense-residual layers: v = requant(A) + sum of the operands, then one clamp.  Hand-worked:
+    the main branch gives 100 (x = 100 through the identity scale); operands (100, -100) leave
+    100, where saturating after the first addition would give 127 - 100 = 27; operands
+    (-128, -128, 127) on a main value of 120 give 120 - 129 = -9."""
+    x = np.array([[[100, 120]]], dtype=np.int8)
+    w = np.ones((1, 1, 1), dtype=np.int8)
+    m, s = _identity_scale(1)
+    r = lambda a, b: np.array([[[a, b]]], dtype=np.int8)
+    y = oracle.conv1d_int8(x, w, None, m, s, [r(100, -128), r(-100, -128), r(0, 127)])
+    assert y.reshape(-1).tolist() == [100, -9]
+    # one operand in a list is the ordinary residual layer; with ReLU the clamp is [0, 127]
+    assert np.array_equal(oracle.conv1d_int8(x, w, None, m, s, [r(5, -7)]), oracle.conv1d_int8(x, w, None, m, s, r(5, -7)))
+    assert oracle.conv1d_int8(x, w, None, m, s, [r(-100, 10), r(-100, 10)], relu=True).reshape(-1).tolist() == [0, 127]
+    # brute force against the big-integer definition on a small dense layer with three operands
+    xs = _draw(5, (2, 3, 9), -128, 127, np.int8)
+    ws = _draw(6, (4, 3, 3), -127, 127, np.int8)
+    bias = _draw(7, (4,), -300, 300, np.int32)
+    mm = _draw(8, (4,), 1 << 30, (1 << 31) - 1, np.int32)
+    ss = np.full(4, 38, np.int32)
+    rs = [_draw(9 + i, (2, 4, 9), -128, 127, np.int8) for i in range(3)]
+    got = oracle.conv1d_int8(xs, ws, bias, mm, ss, rs, pad_left=1, pad_right=1)
+    ref = py_layer(xs.tolist(), ws.tolist(), bias.tolist(), mm.tolist(), ss.tolist(), tuple(r_.tolist() for r_ in rs),
+                   1, 1, 1, 1, False, False)
+    assert got.tolist() == ref
+
+
 # ----------------------------------------------------------------------------- a9 wiring on tiny encoders
 def py_encoder(net, params, x):
     slots = {0: x.tolist()}
     for op, p in zip(net.ops, params):
         res = slots[op.res_slot] if op.res_slot >= 0 else None
+        if getattr(op, "more_res", None):
+            res = (res,) + tuple(slots[r] for r in op.more_res)
         slots[op.out_slot] = py_layer(
             slots[op.in_slot], p["w"].tolist(), None if p["bias"] is None else p["bias"].tolist(),
             p["m"].tolist(), p["s"].tolist(), res, op.stride, op.dilation, op.pad_left, op.pad_right,
@@ -287,7 +318,7 @@ def py_encoder(net, params, x):
     return slots[net.ops[-1].out_slot]
 
 
-@pytest.mark.parametrize("cfg,w_bits", [(0, 8), (1, 8), (2, 8), (3, 8), (4, 8), (6, 8), (1, 6)])
+@pytest.mark.parametrize("cfg,w_bits", [(0, 8), (1, 8), (2, 8), (3, 8), (4, 8), (6, 8), (7, 8), (1, 6)])
 def test_tiny_encoders_match_big_int_composition(cfg, w_bits):
     net = W.tiny_config(cfg)
     for seed in (1, 2):

@@ -90,14 +90,32 @@ def test_variants_of_the_same_families():
     assert big.min() == -31 and big.max() == 31 and len(set(big.reshape(-1).tolist())) == 63
 
 
-@pytest.mark.parametrize("cfg", range(5))
+def test_dense_residual_jasper_wiring():
+    net = W.jasper(1, 1000, config_id=3, dense_residual=True)
+    assert len(net.ops) == 64 + 45                                   # one more projection per earlier block input
+    last = [o for o in net.ops if o.name.endswith(".c4")]
+    assert [len(o.more_res) for o in last] == list(range(10))        # block b adds b earlier inputs
+    proj = [o for o in net.ops if ".res_from" in o.name]
+    assert all(o.k == 1 and not (o.flags & 1) and o.has_bias for o in proj)
+    j5 = [o for o in proj if o.name.startswith("J5.1.")]
+    assert [o.Cin for o in j5] == [256, 256, 256, 384, 384, 512, 512, 640, 640] and all(o.Cout == 768 for o in j5)
+    # BOPs of the dense-residual shape are within 1 % of the paper's Table 1 (10.7 T)
+    assert W.net_macs(net) * 64 / 1e12 == pytest.approx(10.7, rel=0.01)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2, 3, 4, 7])
 def test_slot_wiring_is_hazard_free(cfg):
     """No op writes a slot it reads, slot 0 is never written, and every read slot holds the
     tensor the builder meant (replay with symbolic tensor ids)."""
-    for net in (W.build_config(cfg), W.tiny_config(cfg)):
+    nets = (W.jasper(2, 400, config_id=3, dense_residual=True), W.tiny_config(7)) if cfg == 7 else \
+        (W.build_config(cfg), W.tiny_config(cfg))
+    for net in nets:
         holds = {0: ("x", net.Cin, net.Tin)}
         for i, o in enumerate(net.ops):
             assert o.out_slot != 0 and o.out_slot != o.in_slot and o.out_slot != o.res_slot
+            assert o.out_slot not in o.more_res and len(set(o.more_res + [o.res_slot])) == len(o.more_res) + 1
+            for j, r in enumerate(o.more_res):
+                assert holds[r][1:] == (o.Cout, o.Tout) and holds[r][0].endswith(f".res_from{j}")
             assert o.in_slot in holds
             _, c_in, t_in = holds[o.in_slot]
             assert t_in == o.Tin and c_in >= o.Cin
