@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (default 2); 5 = configuration 4 with its integer activations")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (default 2); 5 = configuration 4 with its integer activations, 6 = configuration 3 with dense residuals")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time separate kernel launches instead of the HIP graph")
@@ -82,6 +82,8 @@ def main():
 
     torch.cuda.set_device(0)
     net = W.build_config(args.config)
+    workload_label = {5: "configs[4] with integer activations",
+                      6: "configs[3] with dense residuals"}.get(args.config, f"configs[{args.config}]")
     params = W.draw_net_params(net, args.seed)
     x_host = W.draw_input(net, args.seed)
 
@@ -91,7 +93,7 @@ def main():
                       o.groups, o.x_batch_stride, 0, o.flags), d["w"], d["bias"], d["m"], d["s"],
             o.in_slot, o.res_slot, o.out_slot,
             Q.make_act(p["act"]["kind"], Q.iexp_init(p["act"]["S"], p["act"]["u"]), p["act"]["m"], p["act"]["s"])
-            if "act" in p else None) for o, d, p in zip(net.ops, dparams, params)]
+            if "act" in p else None, list(o.more_res)) for o, d, p in zip(net.ops, dparams, params)]
     enc = Q.Encoder(ops, net.n_slots)
     ws = torch.empty(max(enc.workspace_bytes, 256), dtype=torch.int8, device="cuda")
     y = torch.empty((net.B, net.Cout, net.Tout), dtype=torch.int8, device="cuda")
@@ -204,7 +206,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": f"{'configs[4] with integer activations' if args.config == 5 else f'configs[{args.config}]'} {net.name} B={net.B} T_in={net.Tin} ({len(net.ops)} ops)",
+        "config": {"workload": f"{workload_label} {net.name} B={net.B} T_in={net.Tin} ({len(net.ops)} ops)",
                    "seed": args.seed, "parallelism": "single GPU",
                    "launch": "separate kernel launches" if args.eager else "HIP graph replay (one launch per step)"},
         "ms_per_step_separate_launches": other_ms,

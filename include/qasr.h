@@ -92,6 +92,18 @@ qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const i
                              const int8_t* residual, int8_t* y, void* stream);
 
 /* Size in bytes of the packed form of a layer's weights (0 on an invalid descriptor). */
+/* The layer with several residual operands (the dense-residual wiring of the Jasper family named
+ * in Sec. 3: a block receives the projected inputs of all earlier blocks).  Reading: every operand
+ * is int8 at the output scale and shaped like y (same batch stride); all are added to the
+ * unsaturated rescaled value, then the one clamp:  v = rescale(A) + sum_r residuals[r].
+ * residuals: HOST array of n_res DEVICE pointers, 0 <= n_res <= QASR_MAX_RESIDUALS (else
+ * QASR_ERR_PARAM); n_res <= 1 is qasr_conv1d_int8.  Otherwise as qasr_conv1d_int8. */
+#define QASR_MAX_RESIDUALS 12
+qasr_status qasr_conv1d_int8_multi(const qasr_conv1d_desc* d, const int8_t* x, const int8_t* w,
+                                   const int32_t* bias, const int32_t* m, const int32_t* s,
+                                   const int8_t* const* residuals, int32_t n_res, int8_t* y,
+                                   void* stream);
+
 size_t qasr_packed_weight_bytes(const qasr_conv1d_desc* d);
 
 /* Re-orders w [Cout,Cin,k] of a groups == 1 layer with Cin % 64 == 0 into the matrix-core operand
@@ -198,6 +210,10 @@ typedef struct {
                                 leaves its Cout/2 channels in the first half of every batch item
                                 of the slot: the next layer reads them as a channel-prefix view
                                 (Cin = Cout/2, x_batch_stride = Cout*Tout).                        */
+  int32_t n_more_res;        /* further residual operands besides res_slot (dense-residual layers,
+                                see qasr_conv1d_int8_multi): 0..QASR_MAX_RESIDUALS-1; needs
+                                res_slot >= 0                                                       */
+  int32_t more_res_slots[QASR_MAX_RESIDUALS - 1];   /* their slots; shaped like the output          */
 } qasr_op;
 
 typedef struct qasr_encoder qasr_encoder; /* opaque host object */

@@ -27,6 +27,7 @@ class ConvDesc(ctypes.Structure):
 
 
 ACT_SIGMOID, ACT_SWISH, ACT_GLU = 1, 2, 3
+MAX_RESIDUALS = 12
 
 
 class IExp(ctypes.Structure):
@@ -42,7 +43,8 @@ class Act(ctypes.Structure):
 class _Op(ctypes.Structure):
     """Mirror of qasr_op."""
     _fields_ = [("d", ConvDesc), ("w", _vp), ("bias", _vp), ("m", _vp), ("s", _vp),
-                ("in_slot", _i32), ("res_slot", _i32), ("out_slot", _i32), ("act", ctypes.POINTER(Act))]
+                ("in_slot", _i32), ("res_slot", _i32), ("out_slot", _i32), ("act", ctypes.POINTER(Act)),
+                ("n_more_res", _i32), ("more_res_slots", _i32 * (MAX_RESIDUALS - 1))]
 
 
 class QasrError(RuntimeError):
@@ -103,6 +105,8 @@ def lib():
         L.qasr_encoder_destroy.argtypes = [_vp]
         L.qasr_conv1d_kernel_name.restype = ctypes.c_char_p
         L.qasr_conv1d_kernel_name.argtypes = [dp]
+        L.qasr_conv1d_int8_multi.restype = _i32
+        L.qasr_conv1d_int8_multi.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), _i32, _vp, _vp]
         L.qasr_iexp_init.restype = _i32
         L.qasr_iexp_init.argtypes = [ctypes.c_double, _i32, ctypes.POINTER(IExp)]
         L.qasr_act_int8.restype = _i32
@@ -154,6 +158,14 @@ def conv1d_int8(d: ConvDesc, x, w, bias, m, s, residual, y):
     """qasr_conv1d_int8 on torch CUDA tensors; y is written in place (asynchronously)."""
     _check(lib().qasr_conv1d_int8(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(m), _ptr(s),
                                   _ptr(residual), _ptr(y), _stream()), "qasr_conv1d_int8")
+    return y
+
+
+def conv1d_int8_multi(d: ConvDesc, x, w, bias, m, s, residuals, y):
+    """qasr_conv1d_int8_multi: the layer with a list of residual operands (all added, one clamp)."""
+    arr = (_vp * max(1, len(residuals)))(*[r.data_ptr() for r in residuals])
+    _check(lib().qasr_conv1d_int8_multi(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(m), _ptr(s), arr,
+                                        len(residuals), _ptr(y), _stream()), "qasr_conv1d_int8_multi")
     return y
 
 
@@ -212,7 +224,8 @@ def softmax_int32(e: IExp, x, y):
 
 class Encoder:
     """qasr_encoder_* handle.  `ops` is a sequence of (ConvDesc, w, bias, m, s, in_slot, res_slot,
-    out_slot[, Act or None]) with torch CUDA tensors, which the handle keeps alive."""
+    out_slot[, Act or None[, list of further residual slots]]) with torch CUDA tensors, which the
+    handle keeps alive."""
 
     def __init__(self, ops: Sequence[tuple], n_slots: int):
         self._keep = [o[1:5] for o in ops]
@@ -221,10 +234,14 @@ class Encoder:
         for i, o in enumerate(ops):
             d, w, bias, m, s, i_s, r_s, o_s = o[:8]
             a = o[8] if len(o) > 8 else None
+            more = list(o[9]) if len(o) > 9 and o[9] else []
             if a is not None:
                 acts.append(a)
+            if len(more) > MAX_RESIDUALS - 1:
+                raise ValueError("too many residual operands")
             arr[i] = _Op(d, w.data_ptr(), bias.data_ptr() if bias is not None else None, m.data_ptr(),
-                         s.data_ptr(), i_s, r_s, o_s, ctypes.pointer(a) if a is not None else None)
+                         s.data_ptr(), i_s, r_s, o_s, ctypes.pointer(a) if a is not None else None,
+                         len(more), (_i32 * (MAX_RESIDUALS - 1))(*more))
         h = _vp()
         _check(lib().qasr_encoder_create(arr, len(ops), n_slots, ctypes.byref(h)), "qasr_encoder_create")
         self._h = h

@@ -72,6 +72,8 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
 enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwMfma, PwTile, PwStream, PwPipe, ConvPipe };
 
 Kernel pick_kernel(const ConvParams& p) {
+  if (p.n_res_more > 0)      // dense-residual layers: the two kernels whose epilogue adds several operands
+    return (!p.depthwise && qasr::conv_pipe_supported(p)) ? Kernel::ConvPipe : Kernel::Generic;
   if (p.depthwise) {
     if (qasr::dw_pipe_supported(p)) return Kernel::DwPipe;
     return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
@@ -125,6 +127,8 @@ struct qasr_encoder {
     ConvParams p;          // pointers to weights/constants filled in; x / res / y set per forward
     int32_t in_slot, res_slot, out_slot;
     Kernel kernel;
+    int32_t n_more_res = 0;
+    int32_t more_res_slots[QASR_MAX_RESIDUALS - 1];
     bool has_act = false;
     qasr::ActParams act;   // applied in place to the output when has_act
   };
@@ -158,6 +162,27 @@ qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const i
   const int64_t ny = (int64_t)(p.B - 1) * p.ybs + (int64_t)p.Cout * p.Tout;
   const int64_t nx = (int64_t)(p.B - 1) * p.xbs + (int64_t)p.Cin * p.Tin;
   if (overlaps(y, ny, x, nx) || (residual && overlaps(y, ny, residual, ny))) return QASR_ERR_ALIAS;
+  return launch(p, (hipStream_t)stream);
+}
+
+qasr_status qasr_conv1d_int8_multi(const qasr_conv1d_desc* d, const int8_t* x, const int8_t* w,
+                                   const int32_t* bias, const int32_t* m, const int32_t* s,
+                                   const int8_t* const* residuals, int32_t n_res, int8_t* y, void* stream) {
+  const qasr_status st = check_desc(d);
+  if (st != QASR_OK) return st;
+  if (!x || !w || !m || !s || !y) return QASR_ERR_NULL;
+  if (n_res < 0 || n_res > QASR_MAX_RESIDUALS) return QASR_ERR_PARAM;
+  if (n_res > 0 && !residuals) return QASR_ERR_NULL;
+  for (int32_t r = 0; r < n_res; ++r)
+    if (!residuals[r]) return QASR_ERR_NULL;
+  ConvParams p = make_params(d, x, w, bias, m, s, n_res > 0 ? residuals[0] : nullptr, y);
+  p.n_res_more = n_res > 1 ? n_res - 1 : 0;
+  for (int32_t r = 1; r < n_res; ++r) p.res_more[r - 1] = residuals[r];
+  const int64_t ny = (int64_t)(p.B - 1) * p.ybs + (int64_t)p.Cout * p.Tout;
+  const int64_t nx = (int64_t)(p.B - 1) * p.xbs + (int64_t)p.Cin * p.Tin;
+  if (overlaps(y, ny, x, nx)) return QASR_ERR_ALIAS;
+  for (int32_t r = 0; r < n_res; ++r)
+    if (overlaps(y, ny, residuals[r], ny)) return QASR_ERR_ALIAS;
   return launch(p, (hipStream_t)stream);
 }
 
@@ -301,6 +326,12 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
         o.res_slot < -1 || o.res_slot >= n_slots)
       return QASR_ERR_PARAM;
     if (o.out_slot == o.in_slot || o.out_slot == o.res_slot) return QASR_ERR_PARAM;
+    if (o.n_more_res < 0 || o.n_more_res > QASR_MAX_RESIDUALS - 1 || (o.n_more_res > 0 && o.res_slot < 0))
+      return QASR_ERR_PARAM;
+    for (int32_t r = 0; r < o.n_more_res; ++r) {
+      const int32_t sl = o.more_res_slots[r];
+      if (sl < 0 || sl >= n_slots || sl == o.out_slot) return QASR_ERR_PARAM;
+    }
     if (o.act) {
       const qasr_status as = check_act(o.act);
       if (as != QASR_OK) return as;
@@ -321,6 +352,10 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     const int32_t Tout = (int32_t)out_len64(&o.d);
     if (o.res_slot >= 0) {
       const SlotState& r = slot[o.res_slot];
+      if (!r.live || r.C != o.d.Cout || r.T != Tout) return QASR_ERR_PARAM;
+    }
+    for (int32_t q = 0; q < o.n_more_res; ++q) {
+      const SlotState& r = slot[o.more_res_slots[q]];
       if (!r.live || r.C != o.d.Cout || r.T != Tout) return QASR_ERR_PARAM;
     }
     slot[o.out_slot].live = true;
@@ -366,6 +401,9 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
       op.d.flags |= QASR_FLAG_W_PACKED;
     }
     op.p = make_params(&op.d, nullptr, w, o.bias, o.m, o.s, nullptr, nullptr);
+    op.n_more_res = o.n_more_res;
+    op.p.n_res_more = o.n_more_res;
+    for (int32_t r = 0; r < o.n_more_res; ++r) op.more_res_slots[r] = o.more_res_slots[r];
     op.kernel = pick_kernel(op.p);
     if (o.act) {
       op.has_act = true;
@@ -405,6 +443,8 @@ static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* 
     p.x = op.in_slot == 0 ? x : ws + e->slot_off[op.in_slot];
     p.res = op.res_slot < 0 ? nullptr : (op.res_slot == 0 ? x : ws + e->slot_off[op.res_slot]);
     p.y = (i + 1 == n) ? y : ws + e->slot_off[op.out_slot];
+    for (int32_t r = 0; r < op.n_more_res; ++r)
+      p.res_more[r] = op.more_res_slots[r] == 0 ? x : ws + e->slot_off[op.more_res_slots[r]];
     if (ev) { const hipError_t re = hipEventRecord(ev[i], st); if (re != hipSuccess) return hip_status(re); }
     const qasr_status s = launch(p, st);
     if (s != QASR_OK) return s;

@@ -20,7 +20,12 @@ struct ConvParams {
   int32_t depthwise;     // 0: groups == 1, 1: groups == Cin == Cout
   int32_t relu;
   int32_t w_packed;      // groups == 1, Cin % 64 == 0: weights are in MFMA operand order (below)
+  // dense-residual layers: further residual operands (same shape and stride as `res`), all added
+  // to the rescaled value before the one clamp; only conv_pipe and conv_generic read them
+  int32_t n_res_more;
+  const int8_t* res_more[11];
 };
+constexpr int kMaxMoreRes = 11;
 
 // Packed weight layout (groups == 1, Cin % 64 == 0): [k][ceil(Cout/16)][Cin/64][64 lanes][16 bytes].
 // Lane l = 16*gi + n of block (j, co16, kc) holds output channel co = 16*co16 + n (zeros beyond

@@ -38,6 +38,9 @@ __global__ __launch_bounds__(256) void conv_generic_kernel(ConvParams p) {
   int32_t v = dyadic_rescale(A, p.m[co], p.s[co]);
   const int64_t o = (int64_t)b * p.ybs + (int64_t)co * p.Tout + to;
   if (p.res) v += (int32_t)p.res[o];
+#pragma unroll
+  for (int r = 0; r < kMaxMoreRes; ++r)
+    if (r < p.n_res_more) v += (int32_t)p.res_more[r][o];
   p.y[o] = (int8_t)clamp_i8(v, p.relu ? 0 : -128);
 }
 

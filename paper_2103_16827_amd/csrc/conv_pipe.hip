@@ -223,10 +223,20 @@ __global__ __launch_bounds__(256) void conv_pipe_kernel(ConvParams p, CpGeom g) 
       if (t >= p.Tout) continue;                    // Tout % 4 == 0: the whole dword is in or out
       uint32_t rr = 0;
       if (p.res) rr = *reinterpret_cast<const uint32_t*>(p.res + orow + t);
+      int32_t radd[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) radd[i] = (int32_t)(int8_t)(rr >> (8 * i));
+#pragma unroll
+      for (int r = 0; r < kMaxMoreRes; ++r)          // dense-residual layers: further operands
+        if (r < p.n_res_more) {
+          const uint32_t rw = *reinterpret_cast<const uint32_t*>(p.res_more[r] + orow + t);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) radd[i] += (int32_t)(int8_t)(rw >> (8 * i));
+        }
       uint32_t pk = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int32_t v = dyadic_rescale(acc[mt][nt][i], mc, sc) + (int32_t)(int8_t)(rr >> (8 * i));
+        const int32_t v = dyadic_rescale(acc[mt][nt][i], mc, sc) + radd[i];
         pk |= (uint32_t)(clamp_i8(v, lo) & 0xff) << (8 * i);
       }
       *reinterpret_cast<uint32_t*>(p.y + orow + t) = pk;
@@ -258,6 +268,8 @@ bool pick(const ConvParams& p, int& MT, int& NT) {
   if (p.Tin % 4 != 0 || p.Tout % 4 != 0 || p.xbs % 4 != 0 || p.ybs % 4 != 0) return false;
   if ((uintptr_t)p.x % 4 || (uintptr_t)p.y % 4 || (uintptr_t)p.w % 16 || (p.res && (uintptr_t)p.res % 4))
     return false;
+  for (int r = 0; r < p.n_res_more; ++r)
+    if ((uintptr_t)p.res_more[r] % 4) return false;
   // the kernel addresses the packed weights with 32-bit offsets
   if ((int64_t)p.k * ((p.Cout + 15) / 16) * (p.Cin / 64) * 1024 > 0x7fffffffLL) return false;
   // frames per tile: 96 or 64 (128 would need all 256 registers and leave one wave per SIMD:

@@ -239,6 +239,8 @@ def build_config(i: int, B: Optional[int] = None) -> NetSpec:
         return jasper(B or 16, 1600, config_id=3)
     if i == 4:
         return conformer_shaped(B or 16, 400, config_id=4)
+    if i == 6:      # not one of the five: configuration 3 with the dense-residual wiring
+        return jasper(B or 16, 1600, config_id=6, name="jasper_dr_10x5", dense_residual=True)
     if i == 5:      # not one of the five: configuration 4 with its integer nonlinearities in place
         return conformer_shaped(B or 16, 400, config_id=5, name="conformer_l_shaped_nonlinear", nonlinear=True)
     raise ValueError(i)

@@ -32,7 +32,10 @@ def gpu_layer(op, B, p, x, residual=None, packed=False):
         w = wp
         d.flags |= Q.FLAG_W_PACKED
     y = torch.full((B, op.Cout, op.Tout), 77, dtype=torch.int8, device="cuda")
-    Q.conv1d_int8(d, dev(x), w, dev(p["bias"]), dev(p["m"]), dev(p["s"]), dev(residual), y)
+    if isinstance(residual, (list, tuple)):
+        Q.conv1d_int8_multi(d, dev(x), w, dev(p["bias"]), dev(p["m"]), dev(p["s"]), [dev(r) for r in residual], y)
+    else:
+        Q.conv1d_int8(d, dev(x), w, dev(p["bias"]), dev(p["m"]), dev(p["s"]), dev(residual), y)
     if p.get("act"):
         a = p["act"]
         Q.act_int8(act_of(a), y, B, op.Cout // 2 if a["kind"] == Q.ACT_GLU else op.Cout, op.Tout, y,
@@ -48,7 +51,7 @@ class GpuNet:
         self.net = net
         self.dev_params = [{k: dev(v) for k, v in p.items() if k != "act"} for p in params]
         ops = [(desc_of(o, net.B), dp["w"], dp["bias"], dp["m"], dp["s"], o.in_slot, o.res_slot, o.out_slot,
-                act_of(p.get("act")))
+                act_of(p.get("act")), list(getattr(o, "more_res", [])))
                for o, dp, p in zip(net.ops, self.dev_params, params)]
         self.enc = Q.Encoder(ops, net.n_slots)
         self.ws = torch.empty(max(self.enc.workspace_bytes, 256), dtype=torch.int8, device="cuda")

@@ -92,6 +92,35 @@ def test_quantiser_arguments_rejected_before_any_launch():
     assert L.qasr_dequantize(f(4096 + 8), 16, 1.0, f(4096), None) == -5       # x over q
 
 
+def test_multi_residual_arguments_rejected_before_any_launch():
+    L = Q.lib()
+    f = ctypes.c_void_p
+    d = make_desc(1, 4, 4, 16)
+    call = lambda rs, n, y=f(1 << 20): L.qasr_conv1d_int8_multi(ctypes.byref(d), f(4096), f(8192), None, f(8192), f(8192),
+                                                                 rs, n, y, None)
+    two = (ctypes.c_void_p * 2)(1 << 21, 1 << 22)
+    assert call(two, -1) == -3
+    assert call(two, Q.MAX_RESIDUALS + 1) == -3
+    assert call(None, 2) == -1
+    assert call((ctypes.c_void_p * 2)(1 << 21, None), 2) == -1
+    assert call((ctypes.c_void_p * 2)(1 << 21, (1 << 20) + 8), 2) == -5          # second operand overlaps y
+    # an op list: further operands need the first one, valid slots, and the output's shape
+    def create(specs, n_slots):
+        arr = (_Op * len(specs))()
+        for i, (dd, i_s, r_s, o_s, more) in enumerate(specs):
+            arr[i] = _Op(dd, 4096, None, 4096, 4096, i_s, r_s, o_s, None, len(more),
+                         (ctypes.c_int32 * (Q.MAX_RESIDUALS - 1))(*more))
+        h = ctypes.c_void_p()
+        st = L.qasr_encoder_create(arr, len(specs), n_slots, ctypes.byref(h))
+        assert not h.value or st == 0
+        return st
+    a = make_desc(1, 4, 4, 10)
+    assert create([(a, 0, -1, 1, []), (a, 1, -1, 2, [1])], 3) == -3              # no first operand
+    assert create([(a, 0, -1, 1, []), (a, 0, 1, 2, [7])], 3) == -3               # slot out of range
+    assert create([(a, 0, -1, 1, []), (a, 0, 1, 2, [2])], 3) == -3               # operand is the output
+    assert create([(a, 0, -1, 1, []), (make_desc(1, 4, 8, 10), 0, -1, 2, []), (a, 0, 1, 3, [2])], 4) == -3   # wrong shape
+
+
 def test_iexp_constants_on_the_host():
     c = Q.iexp_init(0.1, 0)                      # floor(6.93), floor(13.53), floor(0.344 / 0.003585)
     assert (c.u, c.q_ln2, c.q_b, c.q_c) == (0, 6, 13, 95)
@@ -144,7 +173,7 @@ def test_encoder_create_validates_activations_on_the_host():
     def create(act, Cout=4):
         arr = (_Op * 1)()
         arr[0] = _Op(make_desc(1, 4, Cout, 10), 4096, None, 4096, 4096, 0, -1, 1,
-                     ctypes.pointer(act) if act is not None else None)
+                     ctypes.pointer(act) if act is not None else None, 0)
         h = ctypes.c_void_p()
         st = Q.lib().qasr_encoder_create(arr, 1, 2, ctypes.byref(h))
         assert not h.value or st == 0
@@ -157,7 +186,7 @@ def test_encoder_create_validates_activations_on_the_host():
 def _ops(specs):
     arr = (_Op * len(specs))()
     for i, (d, i_s, r_s, o_s) in enumerate(specs):
-        arr[i] = _Op(d, 4096, None, 4096, 4096, i_s, r_s, o_s, None)
+        arr[i] = _Op(d, 4096, None, 4096, 4096, i_s, r_s, o_s, None, 0)
     return arr
 
 

@@ -293,6 +293,8 @@ def check_encoder(net, seed, items=None, **draw_kw):
             slots = {0: x[b:b + 1]}
             for i, (op, p) in enumerate(zip(net.ops, params)):
                 r = slots[op.res_slot] if op.res_slot >= 0 else None
+                if getattr(op, "more_res", None):
+                    r = [r] + [slots[q] for q in op.more_res]
                 got = gpu_layer(op, 1, p, slots[op.in_slot], r, packed=(not op.depthwise and op.k > 1))
                 assert np.array_equal(got, outs[i]), f"first failing op {i} {op.name} ({g.kernels()[i]})"
                 slots[op.out_slot] = outs[i]
@@ -564,3 +566,50 @@ def test_w6a8_six_bit_weight_codes_in_int8_storage(cfg):
     activations keep their range."""
     net = W.build_config(1) if cfg == 1 else W.jasper(2, 400, config_id=3)
     check_encoder(net, 2, w_bits=6, s_lo=34, s_hi=42)
+
+
+@pytest.mark.parametrize("n_res,shape", [
+    (2, dict(B=2, Cin=128, Cout=328, T=428, k=11, packed=True)),       # pipelined dense kernel, ragged tiles
+    (12, dict(B=1, Cin=64, Cout=64, T=96, k=3, packed=True)),          # the maximum number of operands
+    (3, dict(B=2, Cin=20, Cout=7, T=53, k=5, packed=False)),           # general kernel
+    (4, dict(B=2, Cin=16, Cout=16, T=64, k=9, dw=True, packed=False)), # depthwise: general kernel too
+    (5, dict(B=1, Cin=256, Cout=256, T=800, k=1, packed=True)),        # pointwise with several operands
+])
+def test_layers_with_several_residual_operands(n_res, shape):
+    kw = dict(shape)
+    packed, dw = kw.pop("packed"), kw.pop("dw", False)
+    B, Cin, Cout, T, k = kw["B"], kw["Cin"], kw["Cout"], kw["T"], kw["k"]
+    say(f"multi-residual n_res={n_res} {shape}")
+    op = W.OpSpec("mr", Cin, Cout, T, k, 1, 1, (k - 1) // 2, k - 1 - (k - 1) // 2, Cin if dw else 1)
+    x = randint_array(3, (B, Cin, T), -128, 127, np.int8)
+    p = {"w": randint_array(4, (Cout, 1 if dw else Cin, k), -127, 127, np.int8),
+         "bias": randint_array(5, (Cout,), -65536, 65536, np.int32),
+         "m": randint_array(6, (Cout,), 1 << 30, (1 << 31) - 1, np.int32),
+         "s": randint_array(7, (Cout,), 38 if dw else 40, 46, np.int32)}
+    rs = [randint_array(20 + r, (B, Cout, T), -128, 127, np.int8) for r in range(n_res)]
+    ref = oracle.conv1d_int8(x, p["w"], p["bias"], p["m"], p["s"], rs, pad_left=op.pad_left, pad_right=op.pad_right,
+                             groups=op.groups)
+    got = gpu_layer(op, B, p, x, rs, packed=packed)
+    assert np.array_equal(got, ref)
+    assert not np.array_equal(ref, oracle.conv1d_int8(x, p["w"], p["bias"], p["m"], p["s"], rs[0], pad_left=op.pad_left,
+                                                      pad_right=op.pad_right, groups=op.groups))
+
+
+def test_tiny_jasper_with_dense_residuals():
+    net = W.tiny_config(7)
+    params = W.draw_net_params(net, 3, s_lo=37, s_hi=38, bias_mag=300)
+    x = W.draw_input(net, 3)
+    g = GpuNet(net, params)
+    y = g.forward(dev(x)).cpu().numpy()
+    assert np.array_equal(y, oracle.encoder_forward(net, params, x))
+    g.enc.close()
+
+
+def test_jasper_dense_residual_batch2():
+    """The dense-residual variant at a quarter of the frames (same ops: up to 9 further operands)."""
+    net = W.jasper(2, 400, config_id=8, dense_residual=True)
+    y = check_encoder(net, 1)
+    g = GpuNet(net, W.draw_net_params(net, 1))
+    ks = g.kernels()
+    assert all(ks[i] == "conv_pipe" for i, o in enumerate(net.ops) if o.more_res)
+    g.enc.close()
