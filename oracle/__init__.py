@@ -64,6 +64,13 @@ def lib():
         L.qasr_oracle_act.argtypes = [i32, p, i32, i32, i64, i64, i64, i32, i64, i64, i64, i32, i32, p]
         L.qasr_oracle_softmax.restype = None
         L.qasr_oracle_softmax.argtypes = [p, i64, i64, i32, i64, i64, i64, p]
+        L.qasr_oracle_minmax.restype = None
+        L.qasr_oracle_minmax.argtypes = [p, i64, p]
+        L.qasr_oracle_dyadic.restype = i32
+        L.qasr_oracle_dyadic.argtypes = [ctypes.c_double, p, p]
+        L.qasr_oracle_fold_quantize.restype = i32
+        L.qasr_oracle_fold_quantize.argtypes = [p, p, p, p, p, p, ctypes.c_float, i32, i64, ctypes.c_float,
+                                                ctypes.c_float, p, p, p, p, p]
         _lib = L
     return _lib
 
@@ -158,6 +165,40 @@ def dequantize(q, S: float) -> np.ndarray:
     x = np.empty(q.shape, dtype=np.float32)
     lib().qasr_oracle_dequantize(_ptr(q, np.int8), q.size, S, _ptr(x, np.float32))
     return x
+
+
+def minmax(x, start=(np.inf, -np.inf)) -> np.ndarray:
+    """Running (min, max) of float32 values, NaNs skipped."""
+    x = np.ascontiguousarray(x, dtype=np.float32).reshape(-1)
+    mm = np.array(start, dtype=np.float32)
+    lib().qasr_oracle_minmax(_ptr(x, np.float32), x.size, _ptr(mm, np.float32))
+    return mm
+
+
+def dyadic(M: float):
+    """(m, s) with 2^30 <= m < 2^31 and m 2^-s nearest to M."""
+    m, s = ctypes.c_int32(), ctypes.c_int32()
+    if lib().qasr_oracle_dyadic(float(M), ctypes.byref(m), ctypes.byref(s)) != 0:
+        raise ValueError("multiplier has no dyadic form in range")
+    return m.value, s.value
+
+
+def fold_quantize(w, b, gamma, beta, mu, var, eps, S_x, S_y):
+    """BatchNorm folding + per-channel weight quantisation + bias / (m, s) derivation.
+    w float32 [Cout, Cin/groups, k]; returns (q_w int8, bias int32, m, s, S_w float32, n_bad)."""
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    Cout = w.shape[0]
+    per = w.size // Cout
+    f32 = lambda a: None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+    b, gamma, beta, mu, var = f32(b), f32(gamma), f32(beta), f32(mu), f32(var)
+    qw = np.empty(w.shape, dtype=np.int8)
+    bq, m, s = (np.empty(Cout, dtype=np.int32) for _ in range(3))
+    Sw = np.empty(Cout, dtype=np.float32)
+    bad = lib().qasr_oracle_fold_quantize(_ptr(w, np.float32), _ptr(b, np.float32), _ptr(gamma, np.float32),
+                                          _ptr(beta, np.float32), _ptr(mu, np.float32), _ptr(var, np.float32),
+                                          eps, Cout, per, S_x, S_y, _ptr(qw, np.int8), _ptr(bq, np.int32),
+                                          _ptr(m, np.int32), _ptr(s, np.int32), _ptr(Sw, np.float32))
+    return qw, bq, m, s, Sw, int(bad)
 
 
 ACT_SIGMOID, ACT_SWISH, ACT_GLU = 1, 2, 3

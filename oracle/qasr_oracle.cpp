@@ -328,4 +328,80 @@ void qasr_oracle_softmax(const int32_t* x, int64_t rows, int64_t L, int u, int64
     }
 }
 
+
+// ---- offline calibration helpers (Sec. 2.1: S, and so alpha, is pre-computed; Sec. 3.1: the
+// min/max values seen on the calibration data are the clipping range; Sec. 2.2: BatchNorm is
+// folded into the preceding convolution)
+//
+// Observer: running minimum and maximum of a float32 tensor, NaNs skipped; mm[0] and mm[1] hold
+// the extremes seen so far (start them at +inf / -inf).  The clipping range of the symmetric
+// quantiser of Eq. 1 is then alpha = max(-min, max).
+void qasr_oracle_minmax(const float* x, int64_t n, float* mm) {
+    for (int64_t i = 0; i < n; ++i) {
+        const float v = x[i];
+        if (v != v) continue;
+        if (v < mm[0]) mm[0] = v;
+        if (v > mm[1]) mm[1] = v;
+    }
+}
+
+// Dyadic form of a positive real multiplier M (the ratio S_w S_x / S_y of a layer): the integer
+// pair with 2^30 <= m < 2^31 and m 2^-s nearest to M,
+//     s = 30 - floor(log2 M),  m = round(M 2^s)   (and m = 2^31 carries into m = 2^30, s - 1).
+// Returns -1 if M is not positive and finite or s would leave [1, 62].
+int qasr_oracle_dyadic(double M, int32_t* m, int32_t* s) {
+    if (!(M > 0.0) || !std::isfinite(M)) return -1;
+    int e;
+    const double f = std::frexp(M, &e);              // M = f 2^e, 1/2 <= f < 1
+    int64_t mi = (int64_t)std::nearbyint(std::ldexp(f, 31));   // f 2^31 in [2^30, 2^31]
+    int sh = 31 - e;
+    if (mi == (int64_t(1) << 31)) { mi >>= 1; --sh; }
+    if (sh < 1 || sh > 62) return -1;
+    *m = (int32_t)mi; *s = sh;
+    return 0;
+}
+
+// Fold a BatchNorm into the convolution before it and quantise the result for the integer layer.
+// Float model:  y = gamma (conv(x, w) + b - mu) / sqrt(var + eps) + beta.  Per output channel c:
+//     f   = gamma / sqrt(var + eps)                      float32, each operation rounded once
+//     w'  = w f            b' = (b - mu) f + beta        float32, each operation rounded once
+//     S_w = max |w'| / 127                                (per-channel symmetric range, Eq. 1)
+//     q_w = Int(w' / S_w)                                 round to nearest, ties to even
+//     B   = Int(b' / (S_w S_x))                           int32 bias at the accumulator's scale (double)
+//     (m, s) = dyadic(S_w S_x / S_y)                      (double)
+// A channel whose folded weights are all zero gets S_w = 1, q_w = 0.  Returns the number of
+// channels whose multiplier has no dyadic form in range or whose bias leaves int32 (0 = fine).
+int qasr_oracle_fold_quantize(const float* w, const float* b /* or null */, const float* gamma,
+                              const float* beta, const float* mu, const float* var, float eps,
+                              int Cout, int64_t per /* Cin/groups * k */, float S_x, float S_y,
+                              int8_t* qw, int32_t* bias_q, int32_t* m, int32_t* s, float* S_w_out) {
+    int bad = 0;
+    for (int c = 0; c < Cout; ++c) {
+        const float den = std::sqrt(var[c] + eps);
+        const float f = gamma[c] / den;
+        float amax = 0.0f;
+        for (int64_t i = 0; i < per; ++i) {
+            const float wf = w[c * per + i] * f;
+            const float a = wf < 0.0f ? -wf : wf;
+            if (a > amax) amax = a;
+        }
+        const float Sw = amax > 0.0f ? amax / 127.0f : 1.0f;
+        for (int64_t i = 0; i < per; ++i) {
+            const float wf = w[c * per + i] * f;
+            qw[c * per + i] = (int8_t)std::nearbyintf(wf / Sw);
+        }
+        const float b0 = b ? b[c] : 0.0f;
+        const float d = b0 - mu[c];
+        const float t = d * f;
+        const float bf = t + beta[c];
+        const double acc_scale = (double)Sw * (double)S_x;
+        const double bq = std::nearbyint((double)bf / acc_scale);
+        if (!(bq >= -2147483648.0 && bq <= 2147483647.0)) { ++bad; bias_q[c] = 0; }
+        else bias_q[c] = (int32_t)bq;
+        if (qasr_oracle_dyadic(acc_scale / (double)S_y, &m[c], &s[c]) != 0) { ++bad; m[c] = 0; s[c] = 1; }
+        S_w_out[c] = Sw;
+    }
+    return bad;
+}
+
 }  // extern "C"

@@ -544,3 +544,94 @@ def test_iexp_constants_reject_unusable_scales():
     for S, u in [(0.0, 0), (-1.0, 0), (float("nan"), 0), (float("inf"), 0), (1.0, 0), (0.1, -1), (0.1, 17), (1e-9, 8)]:
         with pytest.raises(ValueError):
             oracle.iexp_constants(S, u)
+
+
+# ----------------------------------------------------------------------------- offline calibration helpers
+def test_observer_min_max():
+    x = _draw(3, (100003,), -(1 << 20), 1 << 20, np.int32).astype(np.float32) * np.float32(1e-3)
+    x[[5, 77, 4096]] = np.nan
+    mm = oracle.minmax(x)
+    assert mm[0] == np.nanmin(x) and mm[1] == np.nanmax(x)
+    # running: a second tensor only widens the range; NaNs and an empty tensor change nothing
+    y = np.array([np.nan, 1e9, np.nan], dtype=np.float32)
+    mm2 = oracle.minmax(y, start=mm)
+    assert mm2[0] == mm[0] and mm2[1] == np.float32(1e9)
+    assert oracle.minmax(np.array([np.nan] * 7, dtype=np.float32), start=(3.0, -4.0)).tolist() == [3.0, -4.0]
+    assert oracle.minmax(np.zeros(0, dtype=np.float32)).tolist() == [np.inf, -np.inf]
+    assert oracle.minmax(np.array([-np.inf, 2.5, np.inf], dtype=np.float32)).tolist() == [-np.inf, np.inf]
+    assert oracle.minmax(np.array([1.0, -2.0, 5.0], dtype=np.float32)).tolist() == [-2.0, 5.0]
+
+
+def test_dyadic_form_of_a_multiplier(golden):
+    for row in golden("calibration_vectors.txt"):
+        if row[0] == "dyadic":
+            assert oracle.dyadic(float(row[1])) == (int(row[2]), int(row[3])), row
+    # nearest: |m 2^-s - M| <= 2^-s / 2, exactly, over twelve decades
+    for i, e in enumerate(range(-24, 12)):
+        M = float(_draw(40 + i, (1,), 1 << 20, 1 << 30, np.int64)[0]) * 2.0 ** (e - 25) * 1.0000001
+        m, s = oracle.dyadic(M)
+        assert (1 << 30) <= m < (1 << 31) and 1 <= s <= 62
+        assert abs(Fraction(m, 2 ** s) - Fraction(M)) <= Fraction(1, 2 ** (s + 1))
+    # just below a power of two the mantissa rounds up and carries
+    assert oracle.dyadic(0.5 - 1e-13) == (1 << 30, 31)
+    for bad in (0.0, -1.0, float("nan"), float("inf"), 2.0 ** 31, 2.0 ** -40):
+        with pytest.raises(ValueError):
+            oracle.dyadic(bad)
+
+
+def test_fold_and_quantize_hand_worked(golden):
+    row = [r for r in golden("calibration_vectors.txt") if r[0] == "fold"][0]
+    qw, bq, m, s, Sw, bad = oracle.fold_quantize(np.array([[[1.0, -4.0]]]), [0.5], [2.0], [0.125], [0.25], [3.0], 1.0, 0.5, 0.25)
+    assert bad == 0 and qw.reshape(-1).tolist() == [int(row[1]), int(row[2])]
+    assert (int(bq[0]), int(m[0]), int(s[0])) == (int(row[3]), int(row[4]), int(row[5]))
+    assert Sw[0] == np.float32(4.0) / np.float32(127.0)
+
+
+def test_folded_integer_layer_reproduces_the_float_layer_with_batchnorm():
+    """The point of the helper: conv + BatchNorm in floating point against the integer layer built
+    from its outputs (quantised input, q_w, bias, (m, s)), within the quantisation error."""
+    Cout, Cin, k, T = 6, 5, 3, 40
+    g = lambda sd, shape, lo, hi: _draw(sd, shape, -1000, 1000, np.int32).astype(np.float64) / 1000.0 * (hi - lo) / 2 + (hi + lo) / 2
+    w = g(1, (Cout, Cin, k), -0.5, 0.5); b = g(2, (Cout,), -0.3, 0.3)
+    gamma = g(3, (Cout,), 0.5, 1.5); gamma[1] = -gamma[1]                      # a negative gain flips the channel
+    beta = g(4, (Cout,), -0.4, 0.4); mu = g(5, (Cout,), -0.5, 0.5); var = g(6, (Cout,), 0.2, 2.0)
+    eps = 1e-3
+    x = g(7, (1, Cin, T), -2.0, 2.0)
+    # float model (float64): valid convolution, then BatchNorm
+    yf = np.zeros((1, Cout, T - k + 1))
+    for c in range(Cout):
+        for t in range(T - k + 1):
+            yf[0, c, t] = np.sum(w[c] * x[0, :, t:t + k]) + b[c]
+    yf = gamma[None, :, None] * (yf - mu[None, :, None]) / np.sqrt(var[None, :, None] + eps) + beta[None, :, None]
+    S_x = 2.0 / 127
+    S_y = float(np.abs(yf).max()) / 127
+    qx = oracle.quantize(x.astype(np.float32), 2.0)
+    qw, bq, m, s, Sw, bad = oracle.fold_quantize(w, b, gamma, beta, mu, var, eps, S_x, S_y)
+    assert bad == 0
+    yi = oracle.conv1d_int8(qx, qw, bq, m, s)
+    # input rounding (S_x / 2 per tap through the folded weights), weight rounding (S_w / 2 per tap
+    # on |x| <= 2), the output's own half step; all in units of S_y
+    wf = np.abs(w * (gamma / np.sqrt(var + eps))[:, None, None]).sum(axis=(1, 2))
+    bound = (wf * S_x / 2 + Cin * k * Sw / 2 * 2.0) / S_y + 0.5 + 0.5
+    err = np.abs(yi[0].astype(np.float64) - yf[0] / S_y)
+    assert np.all(err.max(axis=1) <= bound), (err.max(axis=1), bound)
+    assert np.corrcoef(yi.reshape(-1), yf.reshape(-1))[0, 1] > 0.999
+    # every channel uses its full code range, and the scales are the per-channel maxima
+    assert np.all(np.abs(qw.reshape(Cout, -1)).max(axis=1) == 127)
+    f32 = (gamma.astype(np.float32) / np.sqrt(var.astype(np.float32) + np.float32(eps)))
+    assert np.allclose(Sw, np.abs(w.astype(np.float32) * f32[:, None, None]).reshape(Cout, -1).max(axis=1) / 127, rtol=1e-6)
+
+
+def test_fold_with_identity_batchnorm_is_plain_per_channel_quantisation():
+    w = _draw(11, (4, 3, 5), -1000, 1000, np.int32).astype(np.float32) / np.float32(777.0)
+    w[2] = 0.0                                                                  # an all-zero channel
+    one, zero = np.ones(4, np.float32), np.zeros(4, np.float32)
+    qw, bq, m, s, Sw, bad = oracle.fold_quantize(w, None, one, zero, zero, one, 0.0, 0.25, 0.5)
+    assert bad == 0 and np.all(bq == 0) and np.all(qw[2] == 0) and Sw[2] == 1.0
+    for c in (0, 1, 3):
+        Sc = np.abs(w[c]).max() / np.float32(127.0)
+        assert Sw[c] == Sc and np.array_equal(qw[c], np.rint(w[c] / Sc).astype(np.int8))
+        assert (int(m[c]), int(s[c])) == oracle.dyadic(float(Sc) * 0.25 / 0.5)
+    # a multiplier out of range and a bias beyond int32 are counted, not silently wrapped
+    assert oracle.fold_quantize(w[:1], [1e9], one[:1], zero[:1], zero[:1], one[:1], 0.0, 1e-6, 0.5)[5] == 1
+    assert oracle.fold_quantize(w[:1], None, one[:1], zero[:1], zero[:1], one[:1], 0.0, 1e-30, 1.0)[5] == 1
