@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--profile-passes", type=int, default=5, help="per-op timed passes for the roofline")
     ap.add_argument("--softmax", default="", metavar="ROWS,LEN",
                     help="also run 12 qasr_softmax_int32 calls on seeded int32 logits of this shape (for profiler runs)")
+    ap.add_argument("--observer-mib", type=int, default=0,
+                    help="also run 12 qasr_observe_minmax calls on this many MiB of float32 values (for profiler runs)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the steps, run one plain elementwise int8 kernel that reads and writes this many MiB "
                          "(the known-size dispatch that calibrates the HBM byte counters of a --pmc run)")
@@ -135,6 +137,15 @@ def main():
             Q.softmax_int32(e_sm, lg, pr)
         torch.cuda.synchronize()
         del lg, pr
+
+    if args.observer_mib > 0:
+        # a side measurement for profiler runs: the min/max observer on float32 activations
+        act = torch.rand((args.observer_mib << 20) // 4, dtype=torch.float32, device="cuda")
+        mm = torch.tensor([float("inf"), float("-inf")], dtype=torch.float32, device="cuda")
+        for _ in range(12):
+            Q.observe_minmax(act, mm)
+        torch.cuda.synchronize()
+        del act, mm
 
     if args.calib_copy_mib > 0:
         a = torch.zeros(args.calib_copy_mib << 20, dtype=torch.int8, device="cuda")

@@ -142,6 +142,41 @@ qasr_status qasr_quantize(const float* x, size_t n, float alpha, int8_t* q, void
  * QASR_ERR_PARAM; n == 0 is a no-op; x must not overlap q. */
 qasr_status qasr_dequantize(const int8_t* q, size_t n, float S, float* x, void* stream);
 
+/* Offline calibration helpers: what turns a float model and calibration activations into the
+ * constants the integer layers take (Sec. 2.1: S is pre-computed, static quantisation; Sec. 3.1:
+ * the min/max values seen on the calibration data are the clipping range; Sec. 2.2: BatchNorm is
+ * folded into the preceding convolution).  The synthetic calibration data itself (Sec. 2.3) is not
+ * part of this library.
+ *
+ * qasr_observe_minmax: running extremes of n float32 values (device), NaNs skipped:
+ *   minmax[0] = min(minmax[0], min x),  minmax[1] = max(minmax[1], max x)     (minmax: 2 floats,
+ *   device; start them at +inf / -inf; zeros of either sign compare equal).  The symmetric range
+ *   of Eq. 1 is then alpha = max(-minmax[0], minmax[1]).  n == 0 is a no-op.  One kernel. */
+qasr_status qasr_observe_minmax(const float* x, size_t n, float* minmax, void* stream);
+
+/* The dyadic form of a positive real multiplier M (a layer's S_w S_x / S_y): 2^30 <= m < 2^31 and
+ * m 2^-s nearest to M, s = 30 - floor(log2 M).  HOST arithmetic in double precision.
+ * QASR_ERR_PARAM if M is not positive and finite or s would leave [1, 62]. */
+qasr_status qasr_dyadic_from_scale(double M, int32_t* m, int32_t* s);
+
+/* BatchNorm folding and quantisation of one convolution (all pointers DEVICE).  Float model:
+ *   y = gamma (conv(x, w) + conv_bias - mean) / sqrt(var + eps) + beta.        Per channel c:
+ *   f = gamma / sqrt(var + eps);  w' = w f;  b' = (conv_bias - mean) f + beta    (float32, each
+ *                                                        operation rounded once, nothing fused)
+ *   S_w = max|w'| / 127 (1 for an all-zero channel);  q_w = Int(w' / S_w), ties to even  (Eq. 1
+ *   per output channel);  bias_q = Int(b' / (S_w S_x)) int32;  (m, s) = dyadic(S_w S_x / S_y)
+ *   (double precision).
+ * w, q_w: [Cout][per_channel] (per_channel = Cin/groups * k), conv_bias may be NULL (zeros);
+ * gamma, beta, mean, var, bias_q, m, s: [Cout]; S_w: [Cout] float32 or NULL; S_x, S_y: the input
+ * and output activation scales (finite, > 0); eps finite, >= 0.  A channel whose bias leaves
+ * int32 or whose multiplier has no dyadic form gets bias 0 / (m, s) = (0, 1) and adds to
+ * *bad_count (device int32 the caller zeroed, or NULL).  q_w must not overlap w.  One kernel. */
+qasr_status qasr_fold_bn_quantize(const float* w, const float* conv_bias, const float* gamma,
+                                  const float* beta, const float* mean, const float* var, float eps,
+                                  int32_t Cout, int64_t per_channel, float S_x, float S_y,
+                                  int8_t* q_w, int32_t* bias_q, int32_t* m, int32_t* s, float* S_w,
+                                  int32_t* bad_count, void* stream);
+
 /* Integer-only non-linear activations (Sec. 2.2, last sentence; Sec. 3, first paragraph: Sigmoid,
  * Softmax and Swish through second-order polynomials, no floating point executed).  The paper
  * refers to the integer-only Transformer work it cites for the procedure; as restated here:

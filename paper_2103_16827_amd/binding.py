@@ -107,6 +107,13 @@ def lib():
         L.qasr_conv1d_kernel_name.argtypes = [dp]
         L.qasr_conv1d_int8_multi.restype = _i32
         L.qasr_conv1d_int8_multi.argtypes = [dp, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_vp), _i32, _vp, _vp]
+        L.qasr_observe_minmax.restype = _i32
+        L.qasr_observe_minmax.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
+        L.qasr_dyadic_from_scale.restype = _i32
+        L.qasr_dyadic_from_scale.argtypes = [ctypes.c_double, ctypes.POINTER(_i32), ctypes.POINTER(_i32)]
+        L.qasr_fold_bn_quantize.restype = _i32
+        L.qasr_fold_bn_quantize.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, _i32, _i64, ctypes.c_float,
+                                            ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
         L.qasr_iexp_init.restype = _i32
         L.qasr_iexp_init.argtypes = [ctypes.c_double, _i32, ctypes.POINTER(IExp)]
         L.qasr_act_int8.restype = _i32
@@ -195,6 +202,27 @@ def dequantize(q, S: float, x):
     """qasr_dequantize: int8 tensor q -> float32 tensor x of the same number of elements."""
     _check(lib().qasr_dequantize(_ptr(q), q.numel(), S, _ptr(x), _stream()), "qasr_dequantize")
     return x
+
+
+def observe_minmax(x, minmax):
+    """qasr_observe_minmax: widen the running (min, max) in the 2-float tensor `minmax` by float32 tensor x."""
+    _check(lib().qasr_observe_minmax(_ptr(x), x.numel(), _ptr(minmax), _stream()), "qasr_observe_minmax")
+    return minmax
+
+
+def dyadic_from_scale(M: float):
+    """qasr_dyadic_from_scale: (m, s) with 2^30 <= m < 2^31 and m 2^-s nearest to M."""
+    m, s = _i32(), _i32()
+    _check(lib().qasr_dyadic_from_scale(M, ctypes.byref(m), ctypes.byref(s)), "qasr_dyadic_from_scale")
+    return m.value, s.value
+
+
+def fold_bn_quantize(w, conv_bias, gamma, beta, mean, var, eps, S_x, S_y, q_w, bias_q, m, s, S_w=None, bad_count=None):
+    """qasr_fold_bn_quantize on torch CUDA tensors (w float32 [Cout, ...], outputs preallocated)."""
+    Cout = w.shape[0]
+    _check(lib().qasr_fold_bn_quantize(_ptr(w), _ptr(conv_bias), _ptr(gamma), _ptr(beta), _ptr(mean), _ptr(var), eps,
+                                       Cout, w.numel() // Cout, S_x, S_y, _ptr(q_w), _ptr(bias_q), _ptr(m), _ptr(s),
+                                       _ptr(S_w), _ptr(bad_count), _stream()), "qasr_fold_bn_quantize")
 
 
 def iexp_init(S: float, u: int) -> IExp:

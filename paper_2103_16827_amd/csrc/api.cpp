@@ -239,6 +239,36 @@ qasr_status qasr_dequantize(const int8_t* q, size_t n, float S, float* x, void* 
   return hip_status(qasr::launch_dequantize(q, n, S, x, (hipStream_t)stream));
 }
 
+qasr_status qasr_observe_minmax(const float* x, size_t n, float* minmax, void* stream) {
+  if (n == 0) return QASR_OK;
+  if (!x || !minmax) return QASR_ERR_NULL;
+  if (n > ((size_t)1 << 40)) return QASR_ERR_SHAPE;
+  if (overlaps(minmax, 8, x, 4 * (int64_t)n)) return QASR_ERR_ALIAS;
+  return hip_status(qasr::launch_minmax(x, n, minmax, (hipStream_t)stream));
+}
+
+qasr_status qasr_dyadic_from_scale(double M, int32_t* m, int32_t* s) {
+  if (!m || !s) return QASR_ERR_NULL;
+  int32_t mm, ss;
+  if (!qasr::dyadic_from_scale(M, mm, ss)) return QASR_ERR_PARAM;
+  *m = mm;
+  *s = ss;
+  return QASR_OK;
+}
+
+qasr_status qasr_fold_bn_quantize(const float* w, const float* conv_bias, const float* gamma, const float* beta,
+                                  const float* mean, const float* var, float eps, int32_t Cout, int64_t per_channel,
+                                  float S_x, float S_y, int8_t* q_w, int32_t* bias_q, int32_t* m, int32_t* s,
+                                  float* S_w, int32_t* bad_count, void* stream) {
+  if (!w || !gamma || !beta || !mean || !var || !q_w || !bias_q || !m || !s) return QASR_ERR_NULL;
+  if (Cout < 1 || per_channel < 1 || per_channel > ((int64_t)1 << 40) / Cout) return QASR_ERR_SHAPE;
+  if (!(S_x > 0.0f) || !std::isfinite(S_x) || !(S_y > 0.0f) || !std::isfinite(S_y) || !(eps >= 0.0f) || !std::isfinite(eps))
+    return QASR_ERR_PARAM;
+  if (overlaps(q_w, (int64_t)Cout * per_channel, w, 4 * (int64_t)Cout * per_channel)) return QASR_ERR_ALIAS;
+  return hip_status(qasr::launch_fold_quantize(w, conv_bias, gamma, beta, mean, var, eps, Cout, per_channel, S_x, S_y, q_w,
+                                               bias_q, m, s, S_w, bad_count, (hipStream_t)stream));
+}
+
 static qasr_status check_iexp(const qasr_iexp* c) {
   if (!c) return QASR_ERR_NULL;
   if (c->u < 0 || c->u > 16 || c->q_ln2 < 1 || c->q_b < 0 || c->q_b >= ((int64_t)1 << 24) || c->q_c < 0 ||

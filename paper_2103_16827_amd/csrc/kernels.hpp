@@ -75,4 +75,13 @@ hipError_t launch_act(const ActParams& c, const int8_t* x, int8_t* y, int32_t B,
 // rows x L int32 logits -> int8 probabilities at scale 2^-7 (kind, m, s unused).
 hipError_t launch_softmax(const ActParams& c, const int32_t* x, int64_t rows, int32_t L, int8_t* y, hipStream_t st);
 
+// Offline calibration helpers (Sec. 2.1, 2.2, 3.1): running (min, max) of float32 values into
+// mm[0..1] (device); the dyadic form of a positive multiplier (host or device arithmetic, the
+// same function); BatchNorm folding + per-channel weight quantisation + bias and (m, s).
+hipError_t launch_minmax(const float* x, size_t n, float* mm, hipStream_t st);
+bool dyadic_from_scale(double M, int32_t& m, int32_t& s);
+hipError_t launch_fold_quantize(const float* w, const float* b, const float* gamma, const float* beta, const float* mean,
+                                const float* var, float eps, int32_t Cout, int64_t per, float S_x, float S_y, int8_t* qw,
+                                int32_t* bias_q, int32_t* m, int32_t* s, float* S_w, int32_t* bad_count, hipStream_t st);
+
 }  // namespace qasr

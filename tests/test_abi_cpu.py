@@ -121,6 +121,40 @@ def test_multi_residual_arguments_rejected_before_any_launch():
     assert create([(a, 0, -1, 1, []), (make_desc(1, 4, 8, 10), 0, -1, 2, []), (a, 0, 1, 3, [2])], 4) == -3   # wrong shape
 
 
+def test_dyadic_from_scale_on_the_host(golden):
+    for row in golden("calibration_vectors.txt"):
+        if row[0] == "dyadic":
+            assert Q.dyadic_from_scale(float(row[1])) == (int(row[2]), int(row[3])), row
+    assert Q.dyadic_from_scale(0.5 - 1e-13) == (1 << 30, 31)                 # the mantissa carries
+    from fractions import Fraction
+    for e in range(-30, 20):
+        M = 1.2345678901 * 2.0 ** e
+        m, s = Q.dyadic_from_scale(M)
+        assert (1 << 30) <= m < (1 << 31) and abs(Fraction(m, 2 ** s) - Fraction(M)) <= Fraction(1, 2 ** (s + 1))
+    L = Q.lib()
+    m, s = ctypes.c_int32(), ctypes.c_int32()
+    for bad in (0.0, -1.0, float("nan"), float("inf"), 2.0 ** 31, 2.0 ** -40):
+        assert L.qasr_dyadic_from_scale(bad, ctypes.byref(m), ctypes.byref(s)) == -3
+    assert L.qasr_dyadic_from_scale(1.0, None, ctypes.byref(s)) == -1
+
+
+def test_calibration_arguments_rejected_before_any_launch():
+    L = Q.lib()
+    f = ctypes.c_void_p
+    assert L.qasr_observe_minmax(None, 16, f(1 << 20), None) == -1
+    assert L.qasr_observe_minmax(f(4096), 16, None, None) == -1
+    assert L.qasr_observe_minmax(None, 0, None, None) == 0
+    assert L.qasr_observe_minmax(f(4096), 16, f(4096 + 32), None) == -5
+    ptrs = [f(1 << 20), f(2 << 20), f(3 << 20), f(4 << 20), f(5 << 20), f(6 << 20)]
+    outs = [f(7 << 20), f(8 << 20), f(9 << 20), f(10 << 20), None, None]
+    call = lambda w=ptrs[0], g=ptrs[2], eps=1e-5, Cout=4, per=12, Sx=0.1, Sy=0.1, qw=outs[0]: L.qasr_fold_bn_quantize(
+        w, ptrs[1], g, ptrs[3], ptrs[4], ptrs[5], eps, Cout, per, Sx, Sy, qw, outs[1], outs[2], outs[3], None, None, None)
+    assert call(w=None) == -1 and call(g=None) == -1 and call(qw=None) == -1
+    assert call(Cout=0) == -2 and call(per=0) == -2
+    assert call(Sx=0.0) == -3 and call(Sy=float("nan")) == -3 and call(eps=-1.0) == -3 and call(Sx=float("inf")) == -3
+    assert call(qw=f((1 << 20) + 64)) == -5
+
+
 def test_iexp_constants_on_the_host():
     c = Q.iexp_init(0.1, 0)                      # floor(6.93), floor(13.53), floor(0.344 / 0.003585)
     assert (c.u, c.q_ln2, c.q_b, c.q_c) == (0, 6, 13, 95)

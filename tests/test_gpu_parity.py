@@ -613,3 +613,57 @@ def test_jasper_dense_residual_batch2():
     ks = g.kernels()
     assert all(ks[i] == "conv_pipe" for i, o in enumerate(net.ops) if o.more_res)
     g.enc.close()
+
+
+# ----------------------------------------------------------------------------- offline calibration helpers
+@pytest.mark.parametrize("n,offset", [(1, 0), (5, 0), (1000003, 0), (16 * 64 * 1600, 0), (4099, 1), (32 * 512 * 800, 0)])
+def test_observer_matches_oracle(n, offset):
+    say(f"observer n={n} offset={offset}")
+    x = (randint_array(50 + n % 11, (n + offset,), -(1 << 22), 1 << 22, np.int32).astype(np.float32) * np.float32(3e-4))
+    if n > 100:
+        x[[7, n // 2, n - 1]] = np.nan
+        x[n // 3] = np.float32(-2000.5)
+        x[n // 5] = np.float32(1999.25)
+    ref = oracle.minmax(x[offset:])
+    xd = torch.from_numpy(x).cuda()
+    mm = torch.tensor([float("inf"), float("-inf"), 123.0], dtype=torch.float32, device="cuda")
+    Q.observe_minmax(xd[offset:], mm)
+    torch.cuda.synchronize()
+    got = mm.cpu().numpy()
+    assert got[0] == ref[0] and got[1] == ref[1] and got[2] == 123.0
+    # running: a second tensor only widens the range
+    y = torch.tensor([float("nan"), 5000.0, -1.0], dtype=torch.float32, device="cuda")
+    Q.observe_minmax(y, mm)
+    torch.cuda.synchronize()
+    got2 = mm.cpu().numpy()
+    assert got2[0] == min(ref[0], np.float32(-1.0)) and got2[1] == np.float32(5000.0)
+
+
+@pytest.mark.parametrize("Cout,Cin_g,k,with_bias", [(256, 256, 11, True), (512, 1, 51, False), (29, 1024, 1, True), (5, 3, 2, True)])
+def test_fold_and_quantize_matches_oracle(Cout, Cin_g, k, with_bias):
+    say(f"fold Cout={Cout} Cin/g={Cin_g} k={k} bias={with_bias}")
+    f = lambda sd, shape, lo, hi: (randint_array(sd, shape, 0, 1 << 24, np.int32).astype(np.float32) / np.float32(1 << 24)
+                                   * np.float32(hi - lo) + np.float32(lo))
+    w = f(1, (Cout, Cin_g, k), -0.3, 0.3)
+    if Cout > 4:
+        w[3] = 0.0                                              # an all-zero channel
+    b = f(2, (Cout,), -0.5, 0.5) if with_bias else None
+    gamma = f(3, (Cout,), 0.4, 1.6); gamma[0] = -gamma[0]
+    beta, mean, var = f(4, (Cout,), -0.5, 0.5), f(5, (Cout,), -1.0, 1.0), f(6, (Cout,), 0.1, 3.0)
+    eps, S_x, S_y = 1e-3, 4.0 / 127, 6.5 / 127
+    if Cout > 4:
+        beta[2] = np.float32(3e9)                               # a bias that leaves int32: counted, set to 0
+    qw_r, bq_r, m_r, s_r, Sw_r, bad_r = oracle.fold_quantize(w, b, gamma, beta, mean, var, eps, S_x, S_y)
+    d = lambda a: None if a is None else torch.from_numpy(a).cuda()
+    qw = torch.full((Cout * Cin_g * k + 16,), 99, dtype=torch.int8, device="cuda")
+    bq, m, s = (torch.full((Cout,), -1, dtype=torch.int32, device="cuda") for _ in range(3))
+    Sw = torch.zeros(Cout, dtype=torch.float32, device="cuda")
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    Q.fold_bn_quantize(d(w), d(b), d(gamma), d(beta), d(mean), d(var), eps, S_x, S_y, qw, bq, m, s, Sw, bad)
+    torch.cuda.synchronize()
+    got = qw.cpu().numpy()
+    assert np.array_equal(got[:-16].reshape(w.shape), qw_r) and np.all(got[-16:] == 99)
+    assert np.array_equal(bq.cpu().numpy(), bq_r) and np.array_equal(m.cpu().numpy(), m_r) and np.array_equal(s.cpu().numpy(), s_r)
+    assert np.array_equal(Sw.cpu().numpy().view(np.uint32), Sw_r.view(np.uint32))
+    assert int(bad.item()) == bad_r == (1 if Cout > 4 else 0)
+    assert np.all(np.abs(qw_r.reshape(Cout, -1)).max(axis=1)[[c for c in range(Cout) if not (Cout > 4 and c == 3)]] == 127)
