@@ -49,6 +49,7 @@ struct PwpGeom {
   int passes;   // ceil(Cout / 256)
   int co16n;    // ceil(Cout / 16)
   int tiles, tiles_per_xcd;
+  int splits, pps;   // workgroups per tile (each takes pps consecutive passes of the output channels)
 };
 
 __device__ __forceinline__ v2i lds_read_tr8(const unsigned char* p) {
@@ -82,11 +83,17 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   const int n = lane & 15, gi = lane >> 4;
   // Workgroup -> tile: consecutive workgroups go round-robin to the 8 XCDs (one L2 each);
   // neighbouring tiles share the cache lines at their common edge, so each XCD gets a contiguous run.
-  const int tile = (int)(blockIdx.x & 7) * g.tiles_per_xcd + (int)(blockIdx.x >> 3);
-  if ((blockIdx.x >> 3) >= (unsigned)g.tiles_per_xcd || tile >= g.tiles) return;   // whole workgroup
+  // When the tiles alone do not fill the chip, `splits` workgroups share a tile, each with its own
+  // run of passes (the tile's workgroups have the same blockIdx & 7: same XCD, the activation tile
+  // comes out of that L2 for all but the first).
+  const int bx = (int)(blockIdx.x % (unsigned)(8 * g.tiles_per_xcd));
+  const int pb = (int)(blockIdx.x / (unsigned)(8 * g.tiles_per_xcd)) * g.pps;     // first pass of this workgroup
+  const int tile = (bx & 7) * g.tiles_per_xcd + (bx >> 3);
+  if (tile >= g.tiles) return;                                                     // whole workgroup
   const int g0 = tile * MT;
-  // passes in which this wave has channels (>= 1: Cout >= 256); it leaves after them
-  const int P = min(g.passes, (p.Cout - wave * ROWS + 8 * ROWS - 1) / (8 * ROWS));
+  // passes in which this wave has channels (>= 1: Cout >= 256, and a multiple of 256 when split);
+  // it leaves after them
+  const int P = min(g.pps, min(g.passes, (p.Cout - wave * ROWS + 8 * ROWS - 1) / (8 * ROWS)) - pb);
 
   // lane -> (row lane/8 of a block of 8 rows, slot lane%8); the unit in that slot, slot ^ (row & 7),
   // is the same for every block of 8 rows: one lane -> unit map for activation loads, residual
@@ -105,7 +112,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
 
   auto issue_residual = [&](int ps, int par) __attribute__((always_inline)) {   // residual rows of pass ps -> stage[par]
     if (has_res) {
-      const int co_w = (ps * 8 + wave) * ROWS;
+      const int co_w = ((pb + ps) * 8 + wave) * ROWS;
 #pragma unroll
       for (int it = 0; it < 2 * NT; ++it) {
         const int co = co_w + 8 * it + (lane >> 3);
@@ -126,7 +133,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     const int ps = q / KCH, kc = q - ps * KCH;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const int co16 = min((ps * 8 + wave) * NT + nt, g.co16n - 1);
+      const int co16 = min(((pb + ps) * 8 + wave) * NT + nt, g.co16n - 1);
       wb[h][nt] = bload16(wrsrc, wlane, (uint32_t)(co16 * KCH + kc) * 1024u);
     }
     seq += NT;
@@ -139,7 +146,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   for (int ps = 0; ps < P; ++ps) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const int co = min((ps * 8 + wave) * ROWS + 16 * nt + n, p.Cout - 1);
+      const int co = min(((pb + ps) * 8 + wave) * ROWS + 16 * nt + n, p.Cout - 1);
       unsigned char* d = cst0 + (ps * NT + nt) * (3 * 64);
       if (lane < 16) {
         if (p.bias) direct_load4(p.bias + co, d);
@@ -232,7 +239,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   };
   // rows of pass ps out of stage[par]: lane -> (row 8 it + lane/8, slot lane%8)
   auto store_rows = [&](int ps, int par) __attribute__((always_inline)) {
-    const int co_w = (ps * 8 + wave) * ROWS;
+    const int co_w = ((pb + ps) * 8 + wave) * ROWS;
     const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
         p.y + (int64_t)co_w * p.Tout, 0, 0x7ffffff0, 0x00027000);
 #pragma unroll
@@ -386,7 +393,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   wait_vm<0>();   // the clamped tail of the weight stream is still in flight: let it land
 }
 
-struct Choice { int MT, KCH; };
+struct Choice { int MT, KCH, splits; };
 
 size_t lds_bytes(int KCH) { return KCH == 4 ? lds_bytes_c<4>() : lds_bytes_c<8>(); }
 
@@ -419,22 +426,35 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   c.KCH = p.Cin / 64;
   // groups per tile: least makespan over the CUs (one workgroup per CU at a time), with a
   // per-tile overhead worth about one group
+  // and, when the tiles do not fill the CUs, workgroups per tile (each takes passes / splits
+  // passes of 256 channels and loads the tile again).  Rough times in microseconds: start-up 3,
+  // per group 0.3 for the tile load and 0.5 per pass at 512 input channels (half at 256).
+  const int passes = (p.Cout + 8 * ROWS - 1) / (8 * ROWS);
+  const double kscale = c.KCH / 8.0;
   double best = 1e300;
   c.MT = 7;
-  for (int MT = 4; MT <= kMaxMT; ++MT) {
-    const int64_t tiles = (G + MT - 1) / MT;
-    const double cost = (double)((tiles + cus - 1) / cus) * (MT + 1.0);
-    if (cost < best - 1e-9) { best = cost; c.MT = MT; }
+  c.splits = 1;
+  for (int splits = 1; splits <= passes; splits *= 2) {
+    if (passes % splits != 0 || (splits > 1 && p.Cout % (8 * ROWS) != 0)) continue;
+    for (int MT = 4; MT <= kMaxMT; ++MT) {
+      const int64_t wgs = (G + MT - 1) / MT * splits;
+      const double cost = (double)((wgs + cus - 1) / cus) * (3.0 + MT * kscale * (0.3 + 0.5 * (passes / splits)));
+      if (cost < best - 1e-9) { best = cost; c.MT = MT; c.splits = splits; }
+    }
   }
-  if (const char* e = getenv("QASR_PWP_MT")) {            // tuning override
+  if (const char* e = getenv("QASR_PWP_MT")) {            // tuning overrides
     const int mt = atoi(e);
     if (mt >= 4 && mt <= kMaxMT) c.MT = mt;
+  }
+  if (const char* e = getenv("QASR_PWP_SPLIT")) {
+    const int sp = atoi(e);
+    if (sp >= 1 && passes % sp == 0 && (sp == 1 || p.Cout % (8 * ROWS) == 0)) c.splits = sp;
   }
   return lds_bytes(c.KCH) <= 160 * 1024;
 }
 
 template <int MT, int KCH>
-hipError_t launch_t(const ConvParams& p, hipStream_t st) {
+hipError_t launch_t(const ConvParams& p, int splits, hipStream_t st) {
   PwpGeom g;
   g.gpr = p.Tin / 16;
   g.G = p.B * g.gpr;
@@ -442,6 +462,8 @@ hipError_t launch_t(const ConvParams& p, hipStream_t st) {
   g.co16n = (p.Cout + 15) / 16;
   g.tiles = (g.G + MT - 1) / MT;
   g.tiles_per_xcd = (g.tiles + 7) / 8;
+  g.splits = splits;
+  g.pps = g.passes / splits;
   static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
   if (!attr_set) {
     const hipError_t e = hipFuncSetAttribute((const void*)pw_pipe_kernel<MT, KCH>,
@@ -449,7 +471,7 @@ hipError_t launch_t(const ConvParams& p, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  return launch_kernel(pw_pipe_kernel<MT, KCH>, dim3((unsigned)(8 * g.tiles_per_xcd)), dim3(512),
+  return launch_kernel(pw_pipe_kernel<MT, KCH>, dim3((unsigned)(8 * g.tiles_per_xcd * g.splits)), dim3(512),
                        (size_t)lds_bytes_c<KCH>(), st, p, g);
 }
 
@@ -463,7 +485,7 @@ bool pw_pipe_supported(const ConvParams& p) {
 hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st) {
   Choice c;
   if (!pick(p, c, num_cus())) return hipErrorInvalidValue;
-#define QASR_CASE(M, K) if (c.MT == M && c.KCH == K) return launch_t<M, K>(p, st);
+#define QASR_CASE(M, K) if (c.MT == M && c.KCH == K) return launch_t<M, K>(p, c.splits, st);
   QASR_CASE(4, 4) QASR_CASE(5, 4) QASR_CASE(6, 4) QASR_CASE(7, 4)
   QASR_CASE(4, 8) QASR_CASE(5, 8) QASR_CASE(6, 8) QASR_CASE(7, 8)
 #undef QASR_CASE

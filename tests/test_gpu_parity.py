@@ -234,6 +234,22 @@ def test_pipelined_pointwise_layers(kw):
     assert run_layer_case(layer_case(**kw)) == "pw_pipe"
 
 
+@pytest.mark.parametrize("split", [1, 2, 4, 8])
+@pytest.mark.parametrize("case", ["2048_res_mixed", "1024_norelu_ragged_rows"])
+def test_pipelined_pointwise_output_channel_splits(case, split, monkeypatch):
+    """Several workgroups per frame tile, each with its own run of 256-channel passes (what the
+    heuristic chooses when the tiles alone do not fill the chip), forced here."""
+    if case == "2048_res_mixed":
+        op, p, x, r, packed = layer_case(name="pipe_split", B=2, Cin=512, Cout=2048, T=400, res=True, packed=True)
+        p["s"][256 * 3:256 * 4] = draw(7, (256,), 20, 32, np.int32)          # one unpipelined pass in a run
+    else:
+        if split == 8:
+            pytest.skip("4 passes")
+        op, p, x, r, packed = layer_case(name="pipe_split", B=3, Cin=256, Cout=1024, T=336, relu=False, packed=True)
+    monkeypatch.setenv("QASR_PWP_SPLIT", str(split))
+    assert run_layer_case((op, p, x, r, packed)) == "pw_pipe"
+
+
 @pytest.mark.parametrize("slow_passes", [(1,), (0,), (1, 2), (0, 3)])
 def test_pipelined_pointwise_mixed_rescale_forms(slow_passes):
     """Passes whose s values are all >= 33 are pipelined, the others take the 64-bit form right
