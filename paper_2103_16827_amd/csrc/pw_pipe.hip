@@ -427,8 +427,9 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   // groups per tile: least makespan over the CUs (one workgroup per CU at a time), with a
   // per-tile overhead worth about one group
   // and, when the tiles do not fill the CUs, workgroups per tile (each takes passes / splits
-  // passes of 256 channels and loads the tile again).  Rough times in microseconds: start-up 3,
-  // per group 0.3 for the tile load and 0.5 per pass at 512 input channels (half at 256).
+  // passes of 256 channels and loads the tile again).  Times in microseconds fitted to single-layer
+  // measurements at 512 input channels (B=16, T=400; 2048, 1024 and 512 output channels): a
+  // workgroup takes about 6.5 + passes * (0.5 MT + 0.7); the per-pass part halves at 256 channels.
   const int passes = (p.Cout + 8 * ROWS - 1) / (8 * ROWS);
   const double kscale = c.KCH / 8.0;
   double best = 1e300;
@@ -438,7 +439,7 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
     if (passes % splits != 0 || (splits > 1 && p.Cout % (8 * ROWS) != 0)) continue;
     for (int MT = 4; MT <= kMaxMT; ++MT) {
       const int64_t wgs = (G + MT - 1) / MT * splits;
-      const double cost = (double)((wgs + cus - 1) / cus) * (3.0 + MT * kscale * (0.3 + 0.5 * (passes / splits)));
+      const double cost = (double)((wgs + cus - 1) / cus) * (6.5 + (passes / splits) * kscale * (0.5 * MT + 0.7));
       if (cost < best - 1e-9) { best = cost; c.MT = MT; c.splits = splits; }
     }
   }
