@@ -65,17 +65,19 @@ __device__ __forceinline__ void direct_load4(const void* gptr, const unsigned ch
                :: "v"(gptr), "s"(m0v) : "memory");
 }
 
-// LDS: [KCH * 64 rows][128 B]  activation tile (unit u of row r in slot u ^ (r & 7))
+// LDS: [XCH * 64 rows][128 B]  activation tile (unit u of row r in slot u ^ (r & 7)); XCH = KCH up to
+//      512 input channels: the whole tile stays; beyond that a ring of 8 chunks (chunk kc in slot
+//      kc & 7) that the single pass of the workgroup streams through
 //      [8 waves][2][ROWS][128 B] staging: residual rows in, int8 rows out, per wave and pass parity
 //      [8 waves][MAXP][NT][3][16] dwords: bias, m, s of the wave's channels of every pass
 template <int KCH>
-constexpr int lds_bytes_c() { return KCH * 8192 + 8 * 2 * ROWS * 128 + 8 * MAXP * NT * 3 * 64; }
+constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS * 128 + 8 * MAXP * NT * 3 * 64; }
 
 template <int MT, int KCH>
 __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   extern __shared__ __align__(128) unsigned char xs[];
   constexpr int NB = MT * NT;                     // epilogue blocks of a pass
-  static_assert(KCH == 4 || KCH == 8, "epilogue steps per product");
+  static_assert(KCH == 4 || KCH == 8 || KCH == 16 || KCH == 32, "instantiated input widths");
   static_assert(KCH % LOOK == 0, "ring slot of a chunk");
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -103,8 +105,9 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   const bool u_ok = u_l < MT && gq_l < g.G;
   const int b_l = gq_l / g.gpr, t16_l = gq_l - b_l * g.gpr;
   const int64_t yoff_l = (int64_t)b_l * p.ybs + 16 * t16_l;       // of this lane's unit
-  unsigned char* const stage0 = xs + KCH * 8192 + wave * (2 * ROWS * 128);
-  unsigned char* const cst0 = xs + KCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
+  constexpr int XCH = KCH < 8 ? KCH : 8;          // activation chunks resident in LDS
+  unsigned char* const stage0 = xs + XCH * 8192 + wave * (2 * ROWS * 128);
+  unsigned char* const cst0 = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
   const bool has_res = p.res != nullptr;
 
   int seq = 0;                                   // vector-memory requests issued by this wave
@@ -164,7 +167,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   const int8_t* const xsrc = p.x + (int64_t)b_l * p.xbs + (int64_t)(8 * wave + (lane >> 3)) * p.Tin + 16 * t16_l;
   const int64_t xstep = (int64_t)64 * p.Tin;
   auto issue_x = [&](int kc) __attribute__((always_inline)) {
-    if (u_ok) direct_load16(xsrc + kc * xstep, xs + 8 * wave * 128 + kc * 8192);
+    if (u_ok) direct_load16(xsrc + kc * xstep, xs + 8 * wave * 128 + (kc & 7) * 8192);
     mark_x[kc] = ++seq;
   };
   issue_w(0, 0);
@@ -315,7 +318,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
         if (kk + LOOKX < KCH) issue_x(kk + LOOKX);
       }
       {
-        const unsigned char* ab = xs + kk * 8192;
+        const unsigned char* ab = xs + (kk & 7) * 8192;
         // the operand of group mt + 2 is read while groups mt and mt + 1 are multiplied
         v2i ar[3][2];
 #pragma unroll
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
           for (int nt = 0; nt < NT; ++nt) {
             acc[par][mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, wb[h][nt], acc[par][mt][nt], 0, 0, 0);
             if (PREV) {
-              constexpr int R = 8 / KCH;          // steps per product: 8 NB steps over KCH MT NT products
+              constexpr int R = KCH <= 8 ? 8 / KCH : 0;   // steps per product: 8 NB steps over KCH MT NT products
               const int slot = (kk * MT + mt) * NT + nt;
 #pragma unroll
               for (int r = 0; r < R; ++r) step(par ^ 1, slot * R + r, res_tag);
@@ -386,16 +389,26 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     }
   };
   do_pass(0, 0, std::true_type{});
-  for (int ps = 1; ps < P; ps += 2) {
-    do_pass(ps, 1, std::false_type{});
-    if (ps + 1 < P) do_pass(ps + 1, 0, std::false_type{});
+  if constexpr (KCH <= 8) {     // (wider inputs stream through the ring once: one pass per workgroup)
+    for (int ps = 1; ps < P; ps += 2) {
+      do_pass(ps, 1, std::false_type{});
+      if (ps + 1 < P) do_pass(ps + 1, 0, std::false_type{});
+    }
   }
-  wait_vm<0>();   // the clamped tail of the weight stream is still in flight: let it land
+  // The clamped tail of the weight stream is still in flight: let it land.  Its destination registers
+  // must stay the ring's until then (to the compiler an unread asm output is dead at once, and it
+  // would hand the registers to the epilogue's values, which the landing data then overwrites):
+  // the ties keep the ring alive up to this point.
+  wait_vm<0>();
+#pragma unroll
+  for (int h = 0; h < LOOK; ++h)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) tie(wb[h][nt]);
 }
 
 struct Choice { int MT, KCH, splits; };
 
-size_t lds_bytes(int KCH) { return KCH == 4 ? lds_bytes_c<4>() : lds_bytes_c<8>(); }
+size_t lds_bytes(int KCH) { return KCH == 4 ? lds_bytes_c<4>() : lds_bytes_c<8>(); }   // (8 chunks at most are resident)
 
 int num_cus() {
   static int n = 0;
@@ -415,7 +428,8 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   if (getenv("QASR_NO_PW_PIPE")) return false;            // tuning: fall through to the other kernels
   if (p.depthwise || p.k != 1 || p.stride != 1 || p.pl != 0 || p.Tout != p.Tin) return false;
   if (!p.w_packed || p.Tin % 16 != 0) return false;
-  if (p.Cin != 256 && p.Cin != 512) return false;         // instantiated widths
+  if (p.Cin != 256 && p.Cin != 512 && p.Cin != 1024 && p.Cin != 2048) return false;   // instantiated widths
+  if (p.Cin > 512 && p.Cout % (8 * ROWS) != 0) return false;   // streamed input: one pass per workgroup, whole passes only
   if (p.Cout < 8 * ROWS || p.Cout > MAXP * 8 * ROWS) return false;   // every wave has channels in pass 0
   if (p.xbs % 16 != 0 || p.ybs % 16 != 0) return false;
   if ((uintptr_t)p.x % 16 || (uintptr_t)p.y % 16 || (uintptr_t)p.w % 16 || (p.res && (uintptr_t)p.res % 16))
@@ -437,11 +451,15 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   c.splits = 1;
   for (int splits = 1; splits <= passes; splits *= 2) {
     if (passes % splits != 0 || (splits > 1 && p.Cout % (8 * ROWS) != 0)) continue;
+    if (c.KCH > 8 && splits != passes) continue;            // streamed input: exactly one pass per workgroup
     for (int MT = 4; MT <= kMaxMT; ++MT) {
       const int64_t wgs = (G + MT - 1) / MT * splits;
       const double cost = (double)((wgs + cus - 1) / cus) * (6.5 + (passes / splits) * kscale * (0.5 * MT + 0.7));
       if (cost < best - 1e-9) { best = cost; c.MT = MT; c.splits = splits; }
     }
+  }
+  if (passes & (passes - 1)) {                              // (splits run over powers of two)
+    if (c.KCH > 8) return false;
   }
   if (const char* e = getenv("QASR_PWP_MT")) {            // tuning overrides
     const int mt = atoi(e);
@@ -449,7 +467,7 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   }
   if (const char* e = getenv("QASR_PWP_SPLIT")) {
     const int sp = atoi(e);
-    if (sp >= 1 && passes % sp == 0 && (sp == 1 || p.Cout % (8 * ROWS) == 0)) c.splits = sp;
+    if (sp >= 1 && passes % sp == 0 && (sp == 1 || p.Cout % (8 * ROWS) == 0) && c.KCH <= 8) c.splits = sp;
   }
   return lds_bytes(c.KCH) <= 160 * 1024;
 }
@@ -489,6 +507,8 @@ hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st) {
 #define QASR_CASE(M, K) if (c.MT == M && c.KCH == K) return launch_t<M, K>(p, c.splits, st);
   QASR_CASE(4, 4) QASR_CASE(5, 4) QASR_CASE(6, 4) QASR_CASE(7, 4)
   QASR_CASE(4, 8) QASR_CASE(5, 8) QASR_CASE(6, 8) QASR_CASE(7, 8)
+  QASR_CASE(4, 16) QASR_CASE(5, 16) QASR_CASE(6, 16) QASR_CASE(7, 16)
+  QASR_CASE(4, 32) QASR_CASE(5, 32) QASR_CASE(6, 32) QASR_CASE(7, 32)
 #undef QASR_CASE
   return hipErrorInvalidValue;
 }

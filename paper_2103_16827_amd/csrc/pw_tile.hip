@@ -257,7 +257,14 @@ __global__ __launch_bounds__(512) void pw_tile_kernel(ConvParams p, PwtGeom g) {
       if (u_ok && co < p.Cout) *reinterpret_cast<v4i*>(p.y + yoff_l + (int64_t)co * p.Tout) = o;
     }
   }
-  wait_vm<0>();   // the clamped tail of the weight stream is still in flight: let it land
+  // The clamped tail of the weight stream is still in flight: let it land, with the ring's
+  // registers still the ring's (an unread asm output is dead to the compiler, which would reuse
+  // the registers while the data is on its way).
+  wait_vm<0>();
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) tie(wb[h][nt]);
 }
 
 struct Choice { int MT, NT; };

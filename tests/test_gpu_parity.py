@@ -226,6 +226,11 @@ PIPE = [
     dict(name="pipe_512_512_generic_s", B=1, Cin=512, Cout=512, T=320, res=True, s_lo=20, s_hi=40, packed=True),
     dict(name="pipe_256_256_s33", B=2, Cin=256, Cout=256, T=160, s_lo=33, s_hi=34, res=True, packed=True),
     dict(name="pipe_256_768_minus128", B=1, Cin=256, Cout=768, T=480, wmin=-128, packed=True),
+    # 1024 / 2048 input channels: the activation chunks stream through a ring of 8 in LDS
+    dict(name="pipe_2048_512_res", B=2, Cin=2048, Cout=512, T=400, res=True, packed=True),
+    dict(name="pipe_2048_256_norelu_ragged_rows", B=3, Cin=2048, Cout=256, T=176, relu=False, packed=True),
+    dict(name="pipe_1024_1024_generic_s", B=1, Cin=1024, Cout=1024, T=320, res=True, s_lo=20, s_hi=40, packed=True),
+    dict(name="pipe_1024_2048_nobias", B=1, Cin=1024, Cout=2048, T=96, bias=False, packed=True),
 ]
 
 
@@ -273,7 +278,8 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
             elif o.k == 1 and o.Tin % 16 == 0:
                 # pipelined / weights-in-registers kernels for the instantiated widths, else the tile kernels
                 nt = {4: 4 if o.Cout > 256 else 2, 8: 4}.get(o.Cin // 64 if o.Cin % 64 == 0 else 0)
-                if o.Cin in (256, 512) and 256 <= o.Cout <= 2048:
+                if (o.Cin in (256, 512) and 256 <= o.Cout <= 2048) or \
+                        (o.Cin in (1024, 2048) and o.Cout in (256, 512, 1024, 2048)):
                     want = "pw_pipe"          # pipelined-epilogue kernel for the instantiated widths
                 elif nt and o.Cout >= 64 * nt:
                     want = "pw_stream"
