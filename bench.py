@@ -59,6 +59,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (default 2); 5 = configuration 4 with its integer activations, 6 = configuration 3 with dense residuals")
+    ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size (e.g. 1: single-utterance latency)")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--eager", action="store_true", help="time separate kernel launches instead of the HIP graph")
@@ -83,7 +84,7 @@ def main():
     import qasr_workloads as W
 
     torch.cuda.set_device(0)
-    net = W.build_config(args.config)
+    net = W.build_config(args.config, args.batch or None)
     workload_label = {5: "configs[4] with integer activations",
                       6: "configs[3] with dense residuals"}.get(args.config, f"configs[{args.config}]")
     params = W.draw_net_params(net, args.seed)

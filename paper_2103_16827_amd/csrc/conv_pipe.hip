@@ -255,7 +255,7 @@ int lds_rows(const ConvParams& p, int TM) {
 // weight request, loop), and the operand reads of all waves share the unit's LDS port.
 double step_cycles(int MT, int NT, int64_t blocks) {
   const int occ = NT == 4 ? 2 : MT > 4 ? 3 : 4;           // bound by registers
-  const double M = 16.0 * MT * NT, alone = M + 150.0, lds = 40.0 * MT;
+  const double M = 16.0 * MT * NT, alone = M + 150.0, lds = 32.0 * MT;
   auto T = [&](int64_t w) { return w == 0 ? 0.0 : fmax(fmax((double)w * M, alone), (double)w * lds); };
   const int64_t n = (blocks + 255) / 256;                 // workgroups on the busiest unit
   return (double)(n / occ) * T(occ) + T(n % occ);
