@@ -124,6 +124,27 @@ def main():
     ms_per_step, ms_per_step_events = timed(step, args.warmup, args.steps)
     # the other launch mode, for comparison (not the reported value)
     other_ms = None if args.eager else timed(lambda: enc.forward(x, y, ws), 3, max(5, args.steps // 5))[0]
+    # The launch floor of this op list: a graph of as many dependent one-element kernels as the
+    # forward has ops (nothing to compute or move), replayed the same way.  What the step costs
+    # beyond it is what the layers' own work costs.
+    floor_ms = None
+    if not args.eager:
+        one_q = torch.zeros(1, dtype=torch.int8, device="cuda")
+        one_x = torch.zeros(1, dtype=torch.float32, device="cuda")
+        n_launch = enc.n_ops + sum(1 for p in params if "act" in p)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            Q.dequantize(one_q, 1.0, one_x)
+            side.synchronize()
+            tiny = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(tiny, stream=side):
+                for _ in range(n_launch):
+                    Q.dequantize(one_q, 1.0, one_x)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        floor_ms = timed(tiny.replay, 3, args.steps)[0]
+        del tiny
     frames = net.B * net.Tin
     value = frames / (ms_per_step * 1e-3)
 
@@ -222,6 +243,9 @@ def main():
                    "seed": args.seed, "parallelism": "single GPU",
                    "launch": "separate kernel launches" if args.eager else "HIP graph replay (one launch per step)"},
         "ms_per_step_separate_launches": other_ms,
+        "launch_floor": None if floor_ms is None else {
+            "ms_per_step": floor_ms, "kernels": n_launch,
+            "what": "graph replay of that many dependent one-element kernels"},
         "int8_TOPS_useful": 2 * total_macs / (ms_per_step * 1e-3) / 1e12,
         "int8_TOPS_frac_of_peak": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / INT8_PEAK_TOPS,
         "roofline": roofline, "stages": stages, "cpu_baseline": cpu,
