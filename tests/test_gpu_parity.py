@@ -700,3 +700,49 @@ def test_fold_and_quantize_matches_oracle(Cout, Cin_g, k, with_bias):
     assert np.array_equal(Sw.cpu().numpy().view(np.uint32), Sw_r.view(np.uint32))
     assert int(bad.item()) == bad_r == (1 if Cout > 4 else 0)
     assert np.all(np.abs(qw_r.reshape(Cout, -1)).max(axis=1)[[c for c in range(Cout) if not (Cout > 4 and c == 3)]] == 127)
+
+
+# ----------------------------------------------------------------------------- seeded random shapes
+def _random_cases(n, seed):
+    """Seeded layer shapes biased towards the boundaries of the kernels' applicability conditions
+    (multiples of 16 / 64 / 256 and their neighbours), so that every dispatch decision is taken
+    from both sides."""
+    r = randint_array(seed, (n, 12), 0, (1 << 31) - 1, np.int64)
+    near = lambda v, base: int(base + (v % 5) - 2)                       # base-2 .. base+2
+    cases = []
+    for i in range(n):
+        v = [int(t) for t in r[i]]
+        kind = v[0] % 3                                                   # 0 pointwise, 1 depthwise, 2 dense
+        B = [1, 2, 3, 13][v[1] % 4]
+        T = [16, 48, 96, 112, 208, 336][v[2] % 6] + (0 if v[3] % 4 else (v[3] % 7) - 3)
+        cbase = [16, 64, 128, 256, 512][v[4] % 5]
+        Cin = cbase if v[5] % 3 else max(1, near(v[5] // 3, cbase))
+        obase = [16, 64, 256, 512, 1024][v[6] % 5]
+        Cout = obase if v[7] % 3 else max(1, near(v[7] // 3, obase))
+        k = 1 if kind == 0 else [2, 3, 5, 11, 33][v[8] % 5]
+        stride = 1 if v[9] % 4 else 2
+        dil = 1 if v[9] % 5 else 2
+        if kind == 0:
+            stride = dil = 1
+        if kind == 1:
+            Cout = Cin = min(Cin, 96)
+        else:
+            Cin, Cout = min(Cin, 520), min(Cout, 1030)
+            if kind == 2:
+                Cin, Cout = min(Cin, 260), min(Cout, 300)
+        T = max(T, 4)
+        cases.append(dict(name=f"rand{seed}_{i}", B=B, Cin=Cin, Cout=Cout, T=T, k=k, stride=stride, dil=dil, dw=kind == 1,
+                          relu=bool(v[10] & 1), bias=bool(v[10] & 2), res=bool(v[10] & 4),
+                          s_lo=[36, 20, 33][v[11] % 3], s_hi=[44, 40, 34][v[11] % 3],
+                          packed=(kind != 1 and Cin % 64 == 0 and (v[10] >> 3) % 4 != 0)))
+    return cases
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_seeded_random_layer_shapes(seed):
+    kernels = {}
+    for kw in _random_cases(100, seed):
+        k = run_layer_case(layer_case(**kw))
+        kernels[k] = kernels.get(k, 0) + 1
+    say(f"kernels hit: {kernels}")
+    assert len(kernels) >= 6
