@@ -271,6 +271,17 @@ size_t qasr_encoder_workspace_bytes(const qasr_encoder* e);
 qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* The forward from float features to float outputs: Eq. 1's quantiser on x (float32
+ * [B,Cin,Tin], clipping range alpha, see qasr_quantize), the integer encoder, the dequantiser
+ * S_out * q on its output (float32 [B,Cout,Tout], see qasr_dequantize).  The int8 copies of input
+ * and output live in the workspace too: it must hold qasr_encoder_workspace_bytes_f32(e) bytes
+ * (256-byte aligned).  Enqueues n_ops + 2 kernels (plus one per activation) and returns; errors
+ * as for the three calls it is made of. */
+size_t qasr_encoder_workspace_bytes_f32(const qasr_encoder* e);
+qasr_status qasr_encoder_forward_f32(const qasr_encoder* e, const float* x, float alpha, float S_out,
+                                     float* y, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+
 /* The same forward as a HIP graph: one launch replays all n_ops kernels with the pointers given
  * here (x, y and workspace must stay valid and in place as long as the graph is used; their
  * contents may change between launches).  qasr_encoder_graph_create runs one ordinary forward on

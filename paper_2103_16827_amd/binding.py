@@ -114,6 +114,10 @@ def lib():
         L.qasr_fold_bn_quantize.restype = _i32
         L.qasr_fold_bn_quantize.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_float, _i32, _i64, ctypes.c_float,
                                             ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.qasr_encoder_workspace_bytes_f32.restype = ctypes.c_size_t
+        L.qasr_encoder_workspace_bytes_f32.argtypes = [_vp]
+        L.qasr_encoder_forward_f32.restype = _i32
+        L.qasr_encoder_forward_f32.argtypes = [_vp, _vp, ctypes.c_float, ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp]
         L.qasr_iexp_init.restype = _i32
         L.qasr_iexp_init.argtypes = [ctypes.c_double, _i32, ctypes.POINTER(IExp)]
         L.qasr_act_int8.restype = _i32
@@ -283,6 +287,17 @@ class Encoder:
         _check(lib().qasr_encoder_forward(self._h, _ptr(x), _ptr(y), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream()),
                "qasr_encoder_forward")
+        return y
+
+    @property
+    def workspace_bytes_f32(self) -> int:
+        return int(lib().qasr_encoder_workspace_bytes_f32(self._h))
+
+    def forward_f32(self, x, alpha: float, S_out: float, y, workspace):
+        """qasr_encoder_forward_f32: float32 features in, float32 outputs out."""
+        _check(lib().qasr_encoder_forward_f32(self._h, _ptr(x), alpha, S_out, _ptr(y), _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _stream()),
+               "qasr_encoder_forward_f32")
         return y
 
     def forward_timed(self, x, y, workspace):

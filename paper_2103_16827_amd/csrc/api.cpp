@@ -135,6 +135,7 @@ struct qasr_encoder {
   std::vector<Op> ops;
   std::vector<size_t> slot_off;   // byte offset of slot i in the workspace (slot 0 unused)
   size_t ws_bytes = 0;
+  size_t in_elems = 0, out_elems = 0;   // int8 elements of the network input and output
   int8_t* packed = nullptr;       // device: packed weights of all groups == 1 layers
 };
 
@@ -405,6 +406,11 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     off += round256(slot_bytes[sidx]);
   }
   e->ws_bytes = off;
+  e->in_elems = (size_t)ops[0].d.B * slot[0].C * slot[0].T;
+  {
+    const qasr_conv1d_desc& ld = ops[n_ops - 1].d;
+    e->out_elems = (size_t)ld.B * ld.Cout * (size_t)out_len64(&ld);
+  }
 
   // ---- one-time device work: pack the dense k>1 weights
   if (packed_bytes) {
@@ -492,6 +498,23 @@ static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* 
 qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
                                  size_t workspace_bytes, void* stream) {
   return forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+size_t qasr_encoder_workspace_bytes_f32(const qasr_encoder* e) {
+  return e ? e->ws_bytes + round256(e->in_elems) + round256(e->out_elems) : 0;
+}
+
+qasr_status qasr_encoder_forward_f32(const qasr_encoder* e, const float* x, float alpha, float S_out, float* y,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (!e || !x || !y) return QASR_ERR_NULL;
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < qasr_encoder_workspace_bytes_f32(e))
+    return QASR_ERR_WORKSPACE;
+  int8_t* xq = (int8_t*)workspace + e->ws_bytes;
+  int8_t* yq = xq + round256(e->in_elems);
+  qasr_status st = qasr_quantize(x, e->in_elems, alpha, xq, stream);
+  if (st == QASR_OK) st = forward_impl(e, xq, yq, workspace, e->ws_bytes ? e->ws_bytes : workspace_bytes, (hipStream_t)stream, nullptr);
+  if (st == QASR_OK) st = qasr_dequantize(yq, e->out_elems, S_out, y, stream);
+  return st;
 }
 
 qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,

@@ -746,3 +746,23 @@ def test_seeded_random_layer_shapes(seed):
         kernels[k] = kernels.get(k, 0) + 1
     say(f"kernels hit: {kernels}")
     assert len(kernels) >= 6
+
+
+def test_forward_from_float_features_to_float_outputs():
+    """Quantiser, integer encoder and dequantiser in one call against the three oracle steps."""
+    net = W.build_config(1)
+    params = W.draw_net_params(net, 4)
+    alpha, S_out = 3.7, 0.0625
+    xf = _features(net.B * net.Cin * net.Tin, 9, alpha).reshape(net.B, net.Cin, net.Tin)
+    ref = oracle.dequantize(oracle.encoder_forward(net, params, oracle.quantize(xf, alpha)), S_out)
+    g = GpuNet(net, params)
+    ws = torch.empty(g.enc.workspace_bytes_f32, dtype=torch.int8, device="cuda")
+    y = torch.empty((net.B, net.Cout, net.Tout), dtype=torch.float32, device="cuda")
+    g.enc.forward_f32(torch.from_numpy(xf).cuda(), alpha, S_out, y, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    small = torch.empty(g.enc.workspace_bytes_f32 - 256, dtype=torch.int8, device="cuda")
+    with pytest.raises(Q.QasrError) as e:
+        g.enc.forward_f32(torch.from_numpy(xf).cuda(), alpha, S_out, y, small)
+    assert e.value.status == -6
+    g.enc.close()
