@@ -549,7 +549,9 @@ def test_activations_match_oracle(kind, B, C, T, S, u, m, s, layout):
 
 
 @pytest.mark.parametrize("rows,L,S,u", [(1, 1, 0.01, 2), (7, 37, 0.002, 0), (64, 400, 0.01, 2), (3, 1000, 1.0 / 64, 4),
-                                         (2, 16384, 0.004, 1), (1024, 400, 0.0073, 3)])
+                                         (2, 16384, 0.004, 1), (1024, 400, 0.0073, 3),
+                                         (33, 300, 1e-5, 0),        # exponentials beyond 32 bits
+                                         (5, 512, 0.01, 2), (9, 513, 0.01, 2)])
 def test_softmax_matches_oracle(rows, L, S, u):
     say(f"softmax rows={rows} L={L} S={S} u={u}")
     x = randint_array(41 + L, (rows, L), -int(6 / S), int(6 / S), np.int32)
