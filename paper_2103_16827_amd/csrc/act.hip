@@ -274,24 +274,34 @@ __global__ __launch_bounds__(256) void softmax_wave_kernel(ActParams c, const in
                                                            int32_t L, int8_t* __restrict__ y) {
   const int lane = threadIdx.x & 63;
   const int64_t nw = (int64_t)gridDim.x * 4;
-  for (int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); row < rows; row += nw) {
+  auto load_row = [&](int64_t row, int32_t (&v)[8]) {
     const int32_t* xr = x + row * L;
-    int32_t xv[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = lane + 64 * k < L ? xr[lane + 64 * k] : 0;
+  };
+  int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  int32_t xv[8], xn[8];
+  load_row(row, xv);
+  for (; row < rows; row += nw) {
+    const bool more = row + nw < rows;               // the next row of this wave is on its way while this one is worked on
+    if (more) load_row(row + nw, xn);
     long long mx = INT32_MIN, mn = INT32_MAX;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const bool in = lane + 64 * k < L;
-      xv[k] = in ? xr[lane + 64 * k] : 0;
-      if (in) {
+    for (int k = 0; k < 8; ++k)
+      if (lane + 64 * k < L) {
         mx = max(mx, (long long)xv[k]);
         mn = min(mn, (long long)xv[k]);
       }
-    }
     mx = wave_reduce(mx, true);
     mn = -wave_reduce(-mn, true);
     const bool fast = ((mx - mn) << c.u) < (1ll << 31) && c.q_ln2 < (1ll << 30);      // wave-uniform
     if (fast) softmax_wave_row<true>(c, xv, L, lane, y + row * L, mx);
     else softmax_wave_row<false>(c, xv, L, lane, y + row * L, mx);
+    if (more) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) xv[k] = xn[k];
+    }
   }
 }
 
@@ -315,7 +325,7 @@ hipError_t launch_act(const ActParams& c, const int8_t* x, int8_t* y, int32_t B,
 hipError_t launch_softmax(const ActParams& c, const int32_t* x, int64_t rows, int32_t L, int8_t* y, hipStream_t st) {
   if (L <= 512) {
     const int64_t wgs = (rows + 3) / 4;
-    return launch_kernel(softmax_wave_kernel, dim3((unsigned)(wgs < 16384 ? wgs : 16384)), dim3(256), 0, st, c, x, rows, L, y);
+    return launch_kernel(softmax_wave_kernel, dim3((unsigned)(wgs < 2048 ? wgs : 2048)), dim3(256), 0, st, c, x, rows, L, y);
   }
   const unsigned grid = (unsigned)(rows < 8192 ? rows : 8192);
   return launch_kernel(softmax_kernel, dim3(grid), dim3(256), 0, st, c, x, rows, L, y);
