@@ -153,3 +153,13 @@ def test_conformer_even_kernel_padding_and_view():
     dw = net.ops[3]
     assert (dw.k, dw.pad_left, dw.pad_right, dw.Tout) == (32, 15, 16, 400)
     assert dw.Cin == 512 and dw.x_batch_stride == 1024 * 400
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more ends with a message, before any GPU work."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in (r.stderr + r.stdout)
