@@ -17,7 +17,10 @@ HIPCC_FLAGS = [
     # matrix-core results stay in ordinary vector registers (no copies through the accumulator file)
     "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-Wall", "-Wno-unused-command-line-argument",
+    # per-kernel register / scratch / LDS figures as compiler remarks: kept in resource_usage.txt
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+RESOURCES = os.path.join(HERE, "resource_usage.txt")
 
 
 def sources():
@@ -38,9 +41,19 @@ def build(verbose: bool = False) -> str:
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     failed = False
+    remarks = []
     for src, pr in procs:
         out, _ = pr.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and l.strip())
+        remarks += [l for l in out.splitlines() if "[-Rpass-analysis=kernel-resource-usage]" in l]
+        kept, skip = [], 0
+        for l in out.splitlines():
+            if "kernel-resource-usage" in l:
+                skip = 2                       # the remark's echo of the source line and its caret
+            elif skip and (l.lstrip().startswith("|") or "|" in l[:8]):
+                skip -= 1
+            elif "packed-fp32-ops" not in l and l.strip():
+                kept.append(l)
+        out = "\n".join(kept)
         if pr.returncode != 0:
             failed = True
             print(f"--- {src} failed:\n{out}", file=sys.stderr)
@@ -50,6 +63,18 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed")
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     subprocess.check_call(cmd)
+    # one line per kernel: name, then the figures the compiler reported for it
+    recs, cur = [], None
+    for l in remarks:
+        body = l.split("remark:", 1)[1].replace("[-Rpass-analysis=kernel-resource-usage]", "").strip()
+        if body.startswith("Function Name:"):
+            cur = [body[len("Function Name:"):].strip()]
+            recs.append(cur)
+        elif cur is not None and ":" in body:
+            cur.append(body.replace(" ", ""))
+    with open(RESOURCES, "w") as f:
+        for r in recs:
+            f.write(" ".join(r) + "\n")
     return LIB
 
 

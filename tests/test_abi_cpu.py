@@ -265,3 +265,22 @@ def test_kernel_dispatch_names():
     assert Q.conv1d_kernel_name(make_desc(32, 1024, 29, 800, flags=Q.FLAG_W_PACKED)) == "pw_tile"
     assert Q.conv1d_kernel_name(make_desc(1, 5, 5, 9, k=3, stride=2, groups=5)) == "conv_generic"
     assert Q.conv1d_kernel_name(make_desc(1, 5, 7, 9, k=3)) == "conv_generic"
+
+
+def test_no_kernel_uses_scratch_memory():
+    """The kernels count their own outstanding vector-memory requests; a register spill would add
+    scratch loads and stores to that count behind their back.  The build records what the compiler
+    reported per kernel: none may use scratch or spill, and the big pipelined kernels must keep two
+    waves per SIMD."""
+    import os
+    path = os.path.join(os.path.dirname(Q.__file__), "resource_usage.txt")
+    if not os.path.exists(path):
+        pytest.skip("library was not built in this tree")
+    rows = [l.split() for l in open(path) if l.strip()]
+    assert len(rows) >= 100
+    for r in rows:
+        f = dict(kv.split(":", 1) for kv in r[1:])
+        assert f["ScratchSize[bytes/lane]"] == "0" and f["VGPRsSpill"] == "0" and f["SGPRsSpill"] == "0", r[0]
+        assert f["DynamicStack"] == "False", r[0]
+        if "pw_pipe_kernel" in r[0] or "conv_pipe_kernel" in r[0]:
+            assert int(f["VGPRs"]) <= 256 and int(f["Occupancy[waves/SIMD]"]) >= 2, r[0]
