@@ -226,6 +226,8 @@ PIPE = [
     dict(name="pipe_512_512_generic_s", B=1, Cin=512, Cout=512, T=320, res=True, s_lo=20, s_hi=40, packed=True),
     dict(name="pipe_256_256_s33", B=2, Cin=256, Cout=256, T=160, s_lo=33, s_hi=34, res=True, packed=True),
     dict(name="pipe_256_768_minus128", B=1, Cin=256, Cout=768, T=480, wmin=-128, packed=True),
+    dict(name="pipe_512_768_s_50_to_60", B=1, Cin=512, Cout=768, T=208, s_lo=50, s_hi=60, packed=True),   # both sides of s = 55
+    dict(name="pipe_256_1024_s33", B=2, Cin=256, Cout=1024, T=160, s_lo=33, s_hi=33, packed=True),         # smallest short-form shift
     # 1024 / 2048 input channels: the activation chunks stream through a ring of 8 in LDS
     dict(name="pipe_2048_512_res", B=2, Cin=2048, Cout=512, T=400, res=True, packed=True),
     dict(name="pipe_2048_256_norelu_ragged_rows", B=3, Cin=2048, Cout=256, T=176, relu=False, packed=True),
