@@ -61,8 +61,6 @@ def build(verbose: bool = False) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    subprocess.check_call(cmd)
     # one line per kernel: name, then the figures the compiler reported for it
     recs, cur = [], None
     for l in remarks:
@@ -75,6 +73,15 @@ def build(verbose: bool = False) -> str:
     with open(RESOURCES, "w") as f:
         for r in recs:
             f.write(" ".join(r) + "\n")
+    # The pipelined kernels count their own vector-memory requests; a spill adds requests nobody
+    # counted and moves registers that loads in flight still own.  Such a build must never run.
+    spilled = [r[0] for r in recs if not any(x == "ScratchSize[bytes/lane]:0" for x in r)]
+    if spilled:
+        if os.path.exists(LIB):
+            os.remove(LIB)
+        raise RuntimeError("kernels use scratch memory (register spills): " + ", ".join(spilled))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
+    subprocess.check_call(cmd)
     return LIB
 
 
