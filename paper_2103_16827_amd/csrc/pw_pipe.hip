@@ -257,7 +257,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   constexpr int STORE_REQS = 2 * NT;              // requests of one store_rows
   // the epilogue of pass ps on its own
   auto epilogue_alone = [&](int ps, int par, auto fast_tag) __attribute__((always_inline)) {
-    wait_vm_dyn(seq - mark_r[par]);
+    if (has_res) wait_vm_dyn(seq - mark_r[par]);          // residual rows of this pass
     if (has_res) {
 #pragma unroll
       for (int e = 0; e < NB; ++e) {
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
       }
     }
     if (PREV) {
-      wait_vm_dyn(seq - mark_r[par ^ 1]);                   // residual rows of the pass before
+      if (RES) wait_vm_dyn(seq - mark_r[par ^ 1]);          // residual rows of the pass before
       if (RES) rw[0] = *stage_word(par ^ 1, 0);
     }
 

@@ -58,17 +58,25 @@ template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
-// at most n vector-memory operations outstanding (n wave-uniform); anything above 32 waits for all
-__device__ __forceinline__ void wait_vm_dyn(int n) {
-  switch (n) {
-#define QASR_W(N) case N: wait_vm<N>(); break;
-    QASR_W(1) QASR_W(2) QASR_W(3) QASR_W(4) QASR_W(5) QASR_W(6) QASR_W(7) QASR_W(8)
-    QASR_W(9) QASR_W(10) QASR_W(11) QASR_W(12) QASR_W(13) QASR_W(14) QASR_W(15) QASR_W(16)
-    QASR_W(17) QASR_W(18) QASR_W(19) QASR_W(20) QASR_W(21) QASR_W(22) QASR_W(23) QASR_W(24)
-    QASR_W(25) QASR_W(26) QASR_W(27) QASR_W(28) QASR_W(29) QASR_W(30) QASR_W(31) QASR_W(32)
-#undef QASR_W
-    default: wait_vm<0>(); break;
+// at most n vector-memory operations outstanding (n wave-uniform).  `s_waitcnt` takes its count as
+// an immediate, so a run-time count selects among 33 instructions: a balanced tree of scalar
+// comparisons, five on any path (a 33-way switch compiles to a long chain of branches and mask
+// bookkeeping that the pipelined kernels would pay at every chunk).  Exact up to 32; above that,
+// 32 (which is within the bound asked for).
+template <int LO, int HI>
+__device__ __forceinline__ void wait_vm_between(int n) {      // LO <= n < HI
+  if constexpr (HI - LO == 1) {
+    wait_vm<LO>();
+  } else {
+    constexpr int MID = (LO + HI) / 2;
+    if (n < MID) wait_vm_between<LO, MID>(n);
+    else wait_vm_between<MID, HI>(n);
   }
+}
+__device__ __forceinline__ void wait_vm_dyn(int n) {
+  n = __builtin_amdgcn_readfirstlane(n);
+  if (n >= 32) wait_vm<32>();
+  else wait_vm_between<0, 32>(n < 0 ? 0 : n);
 }
 // makes every later use of v depend on this point of the (volatile-ordered) instruction stream
 __device__ __forceinline__ void tie(v4i& v) { asm volatile("" : "+v"(v)); }
