@@ -27,6 +27,12 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip"))) + sorted(glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
+def kernels_using_scratch(recs):
+    """Names of the kernels whose resource record (name, then `Key:value` strings as the compiler
+    printed them, blanks removed) does not say `ScratchSize[bytes/lane]:0`."""
+    return [r[0] for r in recs if "ScratchSize[bytes/lane]:0" not in r[1:]]
+
+
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
@@ -75,7 +81,7 @@ def build(verbose: bool = False) -> str:
             f.write(" ".join(r) + "\n")
     # The pipelined kernels count their own vector-memory requests; a spill adds requests nobody
     # counted and moves registers that loads in flight still own.  Such a build must never run.
-    spilled = [r[0] for r in recs if not any(x == "ScratchSize[bytes/lane]:0" for x in r)]
+    spilled = kernels_using_scratch(recs)
     if spilled:
         if os.path.exists(LIB):
             os.remove(LIB)

@@ -284,3 +284,14 @@ def test_no_kernel_uses_scratch_memory():
         assert f["DynamicStack"] == "False", r[0]
         if "pw_pipe_kernel" in r[0] or "conv_pipe_kernel" in r[0]:
             assert int(f["VGPRs"]) <= 256 and int(f["Occupancy[waves/SIMD]"]) >= 2, r[0]
+
+
+def test_build_refuses_kernels_that_spill():
+    """The pipelined kernels count their own memory requests, so a build in which the compiler
+    spilled registers to scratch memory must not produce a library."""
+    from paper_2103_16827_amd.build import kernels_using_scratch
+    ok = ["k_ok", "TotalSGPRs:73", "VGPRs:249", "ScratchSize[bytes/lane]:0", "Occupancy[waves/SIMD]:2"]
+    bad = ["k_spills", "TotalSGPRs:88", "VGPRs:256", "ScratchSize[bytes/lane]:520", "Occupancy[waves/SIMD]:2"]
+    silent = ["k_without_figure", "VGPRs:12"]
+    assert kernels_using_scratch([ok]) == []
+    assert kernels_using_scratch([ok, bad, silent]) == ["k_spills", "k_without_figure"]
