@@ -101,6 +101,8 @@ def lib():
         L.qasr_encoder_num_ops.argtypes = [_vp]
         L.qasr_encoder_op_kernel.restype = ctypes.c_char_p
         L.qasr_encoder_op_kernel.argtypes = [_vp, _i32]
+        L.qasr_encoder_op_act_fused.restype = _i32
+        L.qasr_encoder_op_act_fused.argtypes = [_vp, _i32]
         L.qasr_encoder_destroy.restype = None
         L.qasr_encoder_destroy.argtypes = [_vp]
         L.qasr_conv1d_kernel_name.restype = ctypes.c_char_p
@@ -282,6 +284,9 @@ class Encoder:
 
     def op_kernel(self, i: int) -> str:
         return lib().qasr_encoder_op_kernel(self._h, i).decode()
+
+    def op_act_fused(self, i: int) -> bool:
+        return lib().qasr_encoder_op_act_fused(self._h, i) == 1
 
     def forward(self, x, y, workspace):
         _check(lib().qasr_encoder_forward(self._h, _ptr(x), _ptr(y), _ptr(workspace),

@@ -54,6 +54,14 @@ __device__ __forceinline__ int32_t rescale_clamp(int32_t v, int32_t m, int32_t s
   return (int32_t)w;
 }
 
+// the table the elementwise kernel builds per workgroup, written out once (for layers whose
+// epilogue applies the activation itself)
+__global__ __launch_bounds__(256) void act_table_kernel(ActParams c, uint8_t* table) {
+  const int q = (int)threadIdx.x - 128;
+  const int32_t sg = sigmoid_code_dev(q, c);
+  table[threadIdx.x] = (uint8_t)rescale_clamp(c.kind == 2 ? q * sg : sg, c.m, c.s);
+}
+
 // x, y: [B][C T] int8 per batch item (strides xbs, ybs); grid = (blocks, B)
 __global__ __launch_bounds__(256) void act_unary_kernel(ActParams c, const int8_t* x, int8_t* y,
                                                         int64_t n, int64_t xbs, int64_t ybs, int vec_ok) {
@@ -306,6 +314,11 @@ __global__ __launch_bounds__(256) void softmax_wave_kernel(ActParams c, const in
 }
 
 }  // namespace
+
+hipError_t launch_act_table(const ActParams& c, uint8_t* table, hipStream_t st) {
+  hipLaunchKernelGGL(act_table_kernel, dim3(1), dim3(256), 0, st, c, table);
+  return hipGetLastError();
+}
 
 hipError_t launch_act(const ActParams& c, const int8_t* x, int8_t* y, int32_t B, int64_t n, int64_t xbs, int64_t ybs,
                       hipStream_t st) {

@@ -101,9 +101,9 @@ const char* kernel_name(Kernel k) {
   }
 }
 
-qasr_status launch(const ConvParams& p, hipStream_t st) {
+qasr_status launch_with(Kernel k, const ConvParams& p, hipStream_t st) {
   hipError_t e;
-  switch (pick_kernel(p)) {
+  switch (k) {
     case Kernel::DwMfma: e = qasr::launch_dw_mfma(p, st); break;
     case Kernel::DwPipe: e = qasr::launch_dw_pipe(p, st); break;
     case Kernel::GemmMfma: e = qasr::launch_gemm_mfma(p, st); break;
@@ -116,6 +116,8 @@ qasr_status launch(const ConvParams& p, hipStream_t st) {
   }
   return hip_status(e);
 }
+
+qasr_status launch(const ConvParams& p, hipStream_t st) { return launch_with(pick_kernel(p), p, st); }
 
 size_t round256(size_t n) { return (n + 255) & ~(size_t)255; }
 
@@ -130,6 +132,7 @@ struct qasr_encoder {
     int32_t n_more_res = 0;
     int32_t more_res_slots[QASR_MAX_RESIDUALS - 1];
     bool has_act = false;
+    bool act_fused = false;   // the layer's own kernel applies it (p.act_lut)
     qasr::ActParams act;   // applied in place to the output when has_act
   };
   std::vector<Op> ops;
@@ -395,6 +398,7 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     const size_t bytes = (size_t)o.d.B * o.d.Cout * Tout;
     if (bytes > slot_bytes[o.out_slot]) slot_bytes[o.out_slot] = bytes;
     if (has_packed_form(&o.d)) packed_bytes += round256(packed_bytes_of(&o.d));
+    if (o.act && o.act->kind != QASR_ACT_GLU) packed_bytes += 256;   // room for a fused activation's table
   }
 
   qasr_encoder* e = new (std::nothrow) qasr_encoder();
@@ -444,6 +448,22 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     if (o.act) {
       op.has_act = true;
       op.act = act_params(o.act->kind, o.act->m, o.act->s, o.act->e);
+      // A unary activation after a layer of the pipelined pointwise kernel is applied in that
+      // kernel's epilogue through a 256-entry table (one int8 output per int8 code), built here
+      // once by the activation's own integer arithmetic; everything else keeps the separate pass.
+      if (o.act->kind != QASR_ACT_GLU) {
+        uint8_t* table = reinterpret_cast<uint8_t*>(e->packed + poff);
+        poff += 256;
+        if (op.kernel == Kernel::PwPipe) {
+          const hipError_t te = qasr::launch_act_table(op.act, table, nullptr);
+          if (te != hipSuccess) {
+            qasr_encoder_destroy(e);
+            return hip_status(te);
+          }
+          op.p.act_lut = table;
+          op.act_fused = true;
+        }
+      }
     }
   }
   if (packed_bytes) {
@@ -466,6 +486,11 @@ const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i) {
   return kernel_name(e->ops[i].kernel);
 }
 
+int32_t qasr_encoder_op_act_fused(const qasr_encoder* e, int32_t i) {
+  if (!e || i < 0 || i >= (int32_t)e->ops.size()) return -1;
+  return e->ops[i].act_fused ? 1 : 0;
+}
+
 static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
                                 size_t workspace_bytes, hipStream_t st, hipEvent_t* ev) {
   if (!e || !x || !y) return QASR_ERR_NULL;
@@ -482,9 +507,12 @@ static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* 
     for (int32_t r = 0; r < op.n_more_res; ++r)
       p.res_more[r] = op.more_res_slots[r] == 0 ? x : ws + e->slot_off[op.more_res_slots[r]];
     if (ev) { const hipError_t re = hipEventRecord(ev[i], st); if (re != hipSuccess) return hip_status(re); }
-    const qasr_status s = launch(p, st);
+    // (the choice depends on the caller's pointers too: a fused activation's table is only read
+    // by the pipelined pointwise kernel, any other choice is followed by the separate pass)
+    const Kernel kk = pick_kernel(p);
+    const qasr_status s = launch_with(kk, p, st);
     if (s != QASR_OK) return s;
-    if (op.has_act) {
+    if (op.has_act && !(op.act_fused && kk == Kernel::PwPipe)) {
       const bool glu = op.act.kind == QASR_ACT_GLU;
       const int64_t n_out = (int64_t)(glu ? p.Cout / 2 : p.Cout) * p.Tout;
       const hipError_t ae = qasr::launch_act(op.act, p.y, p.y, p.B, n_out, p.ybs, p.ybs, st);

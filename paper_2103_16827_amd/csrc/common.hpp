@@ -24,6 +24,9 @@ struct ConvParams {
   // to the rescaled value before the one clamp; only conv_pipe and conv_generic read them
   int32_t n_res_more;
   const int8_t* res_more[11];
+  // unary activation fused into the epilogue: 256 bytes, entry (code + 128) = the activation's int8
+  // output for that int8 code (built once by act_table_kernel); null = none.  Only pw_pipe reads it.
+  const uint8_t* act_lut;
 };
 constexpr int kMaxMoreRes = 11;
 

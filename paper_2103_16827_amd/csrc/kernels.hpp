@@ -70,6 +70,8 @@ struct ActParams {
 };
 // x: B items of n (2 n for GLU: value half, gate half) int8 at stride xbs; y: B items of n int8
 // at stride ybs; y may be x itself when the strides are equal.
+// table[code + 128] = int8 output of the unary activation (sigmoid, swish) for every int8 code
+hipError_t launch_act_table(const ActParams& c, uint8_t* table, hipStream_t st);
 hipError_t launch_act(const ActParams& c, const int8_t* x, int8_t* y, int32_t B, int64_t n, int64_t xbs,
                       int64_t ybs, hipStream_t st);
 // rows x L int32 logits -> int8 probabilities at scale 2^-7 (kind, m, s unused).

@@ -70,8 +70,9 @@ __device__ __forceinline__ void direct_load4(const void* gptr, const unsigned ch
 //      kc & 7) that the single pass of the workgroup streams through
 //      [8 waves][2][ROWS][128 B] staging: residual rows in, int8 rows out, per wave and pass parity
 //      [8 waves][MAXP][NT][3][16] dwords: bias, m, s of the wave's channels of every pass
+//      [8 waves][256 B] the fused activation's table (one copy per wave: no barrier needed)
 template <int KCH>
-constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS * 128 + 8 * MAXP * NT * 3 * 64; }
+constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS * 128 + 8 * MAXP * NT * 3 * 64 + 8 * 256; }
 
 template <int MT, int KCH>
 __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
@@ -109,6 +110,8 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   unsigned char* const stage0 = xs + XCH * 8192 + wave * (2 * ROWS * 128);
   unsigned char* const cst0 = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
   const bool has_res = p.res != nullptr;
+  unsigned char* const lutw = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + 8 * (MAXP * NT * 3 * 64) + wave * 256;
+  const bool has_act = p.act_lut != nullptr;        // a unary activation follows the clamp
 
   int seq = 0;                                   // vector-memory requests issued by this wave
   int mark_r[2] = {0, 0}, mark_c = 0, mark_w[LOOK] = {}, mark_x[KCH] = {};
@@ -159,6 +162,10 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
       seq += p.bias ? 3 : 2;
     }
   }
+  if (has_act) {                                   // 64 lanes x 4 bytes: the wave's copy of the table
+    direct_load4(p.act_lut + 4 * lane, lutw);
+    ++seq;
+  }
   mark_c = seq;
   // Activation chunk kc of this wave: rows 64 kc + 8 wave + (0..7).  Only the first LOOKX chunks are
   // requested here, chunk kc + LOOKX during chunk step kc of pass 0: all workgroups start
@@ -198,7 +205,13 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     const uint32_t rw = RES ? *sp : 0u;
     const v4i av = acc[par][mt][nt];
     const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
-    *sp = requant_pack4<FAST, RES>(a4, mc[nt], sh[nt], rnd[nt], rw, lo, hi127);
+    uint32_t pk = requant_pack4<FAST, RES>(a4, mc[nt], sh[nt], rnd[nt], rw, lo, hi127);
+    if (has_act) {                                 // table[code + 128], byte by byte
+      const uint32_t c = pk ^ 0x80808080u;
+      pk = (uint32_t)lutw[c & 0xffu] | ((uint32_t)lutw[(c >> 8) & 0xffu] << 8) |
+           ((uint32_t)lutw[(c >> 16) & 0xffu] << 16) | ((uint32_t)lutw[c >> 24] << 24);
+    }
+    *sp = pk;
   };
   // The pipelined case (short-form rescale, relu): the epilogue of a pass is a stream of 4 NB
   // "elements" (element x = accumulator register x % 4 of block x / 4), each going through six
@@ -381,7 +394,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
       sh[nt] = all_fast ? s_[nt] - 32 : s_[nt];
       rnd[nt] = all_fast ? 1 << ((s_[nt] - 33) & 31) : 0;
     }
-    if (all_fast && p.relu && ps + 1 < P) {
+    if (all_fast && p.relu && !has_act && ps + 1 < P) {
       pending = true;
     } else {
       pending = false;

@@ -49,6 +49,7 @@ class GpuNet:
 
     def __init__(self, net, params):
         self.net = net
+        self.params = params
         self.dev_params = [{k: dev(v) for k, v in p.items() if k != "act"} for p in params]
         ops = [(desc_of(o, net.B), dp["w"], dp["bias"], dp["m"], dp["s"], o.in_slot, o.res_slot, o.out_slot,
                 act_of(p.get("act")), list(getattr(o, "more_res", [])))

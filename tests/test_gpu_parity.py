@@ -586,6 +586,55 @@ def test_conformer_shaped_batch16_with_integer_activations():
     check_encoder(W.build_config(5), 1, items=[0, 15])
 
 
+def test_which_activations_run_inside_the_layer_kernel():
+    """Swish after the 512 -> 2048 layers goes through the pointwise kernel's epilogue table; the
+    Swish after the depthwise convolution and the GLU keep the separate in-place pass (the parity
+    test above covers both routes: it runs this very encoder)."""
+    net = W.build_config(5)
+    g = GpuNet(net, W.draw_net_params(net, 1))
+    kinds = {}
+    for i, (op, p) in enumerate(zip(net.ops, g.params)):
+        a = p.get("act")
+        if a:
+            kinds.setdefault((a["kind"], g.kernels()[i], g.enc.op_act_fused(i)), 0)
+            kinds[(a["kind"], g.kernels()[i], g.enc.op_act_fused(i))] += 1
+        else:
+            assert not g.enc.op_act_fused(i)
+    assert kinds[(Q.ACT_SWISH, "pw_pipe", True)] == 17
+    assert kinds[(Q.ACT_GLU, "pw_pipe", False)] == 17
+    assert sum(n for (k, kern, fused), n in kinds.items() if k == Q.ACT_SWISH and not fused) == 17
+    g.enc.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed", [1, 2])
+def test_fused_activation_with_relu_residual_and_several_passes(seed):
+    """Table lookups in the pointwise kernel's epilogue next to everything else that epilogue does:
+    ReLU before the activation, a residual operand, two passes of output channels, both unary kinds."""
+    from qasr_workloads.nets import _Builder
+    b = _Builder("fused_act_probe", 99, 3, 256, 160)
+    b.op("p1", 256, relu=True)
+    t2 = b.op("p2", 512, relu=True, act=Q.ACT_SIGMOID)
+    b.op("p3", 512, relu=False, act=Q.ACT_SWISH)
+    b.op("p4", 512, relu=True, res=t2, act=Q.ACT_SIGMOID)
+    b.op("p5", 256, relu=False)
+    net = b.done()
+    params = W.draw_net_params(net, seed)
+    for p in params:                       # a sigmoid code has 15 fraction bits: bring it to int8 range
+        if p.get("act") and p["act"]["kind"] == Q.ACT_SIGMOID:
+            p["act"]["s"] = 39
+    x = W.draw_input(net, seed)
+    ref, outs = oracle.encoder_forward(net, params, x, keep=True)
+    for o, a in zip(net.ops, outs):
+        assert len(set(a.reshape(-1).tolist())) > 16, f"degenerate reference output of {o.name}"
+    g = GpuNet(net, params)
+    assert g.kernels() == ["pw_pipe"] * 5
+    assert [g.enc.op_act_fused(i) for i in range(5)] == [False, True, True, True, False]
+    y = g.forward(dev(x)).cpu().numpy()
+    g.enc.close()
+    assert np.array_equal(y, ref)
+
+
 # ----------------------------------------------------------------------------- variants of the same families
 def test_quartznet_10x5():
     """The medium model of the latency comparison (Sec. 3.2): each block type twice."""
