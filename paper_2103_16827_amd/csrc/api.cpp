@@ -87,6 +87,9 @@ Kernel pick_kernel(const ConvParams& p) {
   return Kernel::Generic;
 }
 
+// kernels whose epilogue applies a unary activation's table (ConvParams::act_lut)
+bool applies_act_table(Kernel k) { return k == Kernel::PwPipe || k == Kernel::DwPipe; }
+
 const char* kernel_name(Kernel k) {
   switch (k) {
     case Kernel::DwMfma: return "dw_mfma";
@@ -448,13 +451,13 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     if (o.act) {
       op.has_act = true;
       op.act = act_params(o.act->kind, o.act->m, o.act->s, o.act->e);
-      // A unary activation after a layer of the pipelined pointwise kernel is applied in that
-      // kernel's epilogue through a 256-entry table (one int8 output per int8 code), built here
+      // A unary activation after a layer of the pipelined pointwise or depthwise kernel is applied in
+      // that kernel's epilogue through a 256-entry table (one int8 output per int8 code), built here
       // once by the activation's own integer arithmetic; everything else keeps the separate pass.
       if (o.act->kind != QASR_ACT_GLU) {
         uint8_t* table = reinterpret_cast<uint8_t*>(e->packed + poff);
         poff += 256;
-        if (op.kernel == Kernel::PwPipe) {
+        if (applies_act_table(op.kernel)) {
           const hipError_t te = qasr::launch_act_table(op.act, table, nullptr);
           if (te != hipSuccess) {
             qasr_encoder_destroy(e);
@@ -508,11 +511,11 @@ static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* 
       p.res_more[r] = op.more_res_slots[r] == 0 ? x : ws + e->slot_off[op.more_res_slots[r]];
     if (ev) { const hipError_t re = hipEventRecord(ev[i], st); if (re != hipSuccess) return hip_status(re); }
     // (the choice depends on the caller's pointers too: a fused activation's table is only read
-    // by the pipelined pointwise kernel, any other choice is followed by the separate pass)
+    // by the two pipelined kernels, any other choice is followed by the separate pass)
     const Kernel kk = pick_kernel(p);
     const qasr_status s = launch_with(kk, p, st);
     if (s != QASR_OK) return s;
-    if (op.has_act && !(op.act_fused && kk == Kernel::PwPipe)) {
+    if (op.has_act && !(op.act_fused && applies_act_table(kk))) {
       const bool glu = op.act.kind == QASR_ACT_GLU;
       const int64_t n_out = (int64_t)(glu ? p.Cout / 2 : p.Cout) * p.Tout;
       const hipError_t ae = qasr::launch_act(op.act, p.y, p.y, p.B, n_out, p.ybs, p.ybs, st);

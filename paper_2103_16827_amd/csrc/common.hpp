@@ -25,7 +25,7 @@ struct ConvParams {
   int32_t n_res_more;
   const int8_t* res_more[11];
   // unary activation fused into the epilogue: 256 bytes, entry (code + 128) = the activation's int8
-  // output for that int8 code (built once by act_table_kernel); null = none.  Only pw_pipe reads it.
+  // output for that int8 code (built once by act_table_kernel); null = none.  Only pw_pipe and dw_pipe read it.
   const uint8_t* act_lut;
 };
 constexpr int kMaxMoreRes = 11;

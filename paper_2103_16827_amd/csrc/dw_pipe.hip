@@ -51,13 +51,15 @@ struct DwpGeom {
   int tiles;      // 256-frame tiles per iteration: ceil(R * G / 16) <= kMaxTiles
   int spw;        // rows per wave (a multiple of R)
   int c_per_xcd;  // channels per XCD: ceil(C / 8)
-  int dbg;        // tuning: 1 skip the tiles
 };
 
-template <int KC, int R, int NI>
+// ACT: a unary activation's table is applied after the clamp (its own instantiation: the plain
+// layers keep their code as it is)
+template <int KC, int R, int NI, bool ACT>
 __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
   extern __shared__ __align__(16) unsigned char strips_lds[];      // [4 waves][3 buffers][R][NCH][16]
   __shared__ __align__(16) unsigned char a_lds[KC * 1024];         // A operand, register layout
+  __shared__ __align__(16) unsigned char lut_lds[ACT ? 4 * 256 : 16];   // a fused activation's table, one copy per wave
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -115,6 +117,11 @@ __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
   if (p.bias) bias = gload4(p.bias + c);
   int32_t wj = 0;
   if (tid < p.k) wj = gload_i8(p.w + (int64_t)c * p.k + tid);
+  // a unary activation applied after the clamp: its 256-entry table (int8 output per int8 code),
+  // 64 lanes x 4 bytes straight into this wave's copy; one more request ahead of the rows
+  constexpr bool has_act = ACT;
+  unsigned char* const lutw = lut_lds + (ACT ? wave * 256 : 0);
+  if (has_act) direct_load4(p.act_lut + 4 * lane, lutw);
   int n_rows = 0;                               // row requests of this wave so far
   // Only the first iteration's rows are requested now, the other two after the operand is built:
   // all waves of the chip start together, and a request waits behind everything that entered
@@ -191,7 +198,6 @@ __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
     const unsigned char* const rows_lds = my + buf * R * rowbytes;
     wait_vm_dyn(2 * L + min(it, 2) * 2 * NP);      // the rows of this iteration are in LDS
     asm volatile("" ::: "memory");
-    if (g.dbg & 1) { issue(row + 3 * R, buf); return; }
 
     const int Rv = min(R, s_end - row);
     const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
@@ -218,7 +224,12 @@ __global__ __launch_bounds__(256) void dw_pipe_kernel(ConvParams p, DwpGeom g) {
       for (int e = 0; e < 2; ++e) {
         const v4i av = acc[q & 1][e];
         const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
-        const uint32_t pk = requant_pack4<FAST, false>(a4, mc, sh, rnd, 0u, lo, hi127);
+        uint32_t pk = requant_pack4<FAST, false>(a4, mc, sh, rnd, 0u, lo, hi127);
+        if (has_act) {                               // table[code + 128], byte by byte
+          const uint32_t cd = pk ^ 0x80808080u;
+          pk = (uint32_t)lutw[cd & 0xffu] | ((uint32_t)lutw[(cd >> 8) & 0xffu] << 8) |
+               ((uint32_t)lutw[(cd >> 16) & 0xffu] << 16) | ((uint32_t)lutw[cd >> 24] << 24);
+        }
         __builtin_amdgcn_raw_buffer_store_b32(pk, yrs, out_off[2 * q + e], 0, kStoreThrough);
       }
     };
@@ -272,8 +283,6 @@ bool plan(const ConvParams& p, DwpGeom& g, Plan& pl) {
   pl.NI = (g.NCH + 63) / 64;
   if (pl.NI > 2) return false;                          // longer rows: dw_mfma.hip cuts them up
   g.c_per_xcd = (p.Cout + 7) / 8;
-  g.dbg = 0;
-  if (const char* e = getenv("QASR_DWP_DBG")) g.dbg = atoi(e);
 
   // Batch splits S (workgroups per channel) and rows per iteration R.  Measured on the 512- and
   // 256-channel layers at batch 32: about 1024 workgroups (4 waves per SIMD) with one row per
@@ -308,7 +317,8 @@ hipError_t launch_t(const ConvParams& p, const DwpGeom& g, hipStream_t st) {
   const unsigned gy = (unsigned)((p.B + 4 * g.spw - 1) / (4 * g.spw));
   const dim3 grid(8 * g.c_per_xcd, gy);
   const size_t shmem = (size_t)4 * 3 * R * g.NCH * 16;
-  return launch_kernel(dw_pipe_kernel<KC, R, NI>, grid, dim3(256), shmem, st, p, g);
+  if (p.act_lut) return launch_kernel(dw_pipe_kernel<KC, R, NI, true>, grid, dim3(256), shmem, st, p, g);
+  return launch_kernel(dw_pipe_kernel<KC, R, NI, false>, grid, dim3(256), shmem, st, p, g);
 }
 
 template <int KC>

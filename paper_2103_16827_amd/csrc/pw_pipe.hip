@@ -57,14 +57,6 @@ __device__ __forceinline__ v2i lds_read_tr8(const unsigned char* p) {
       (v2i __attribute__((address_space(3)))*)(const_cast<unsigned char*>(p)));
 }
 
-// One dword per active lane from per-lane global addresses to LDS at lds_wave_base + 4 * lane.
-__device__ __forceinline__ void direct_load4(const void* gptr, const unsigned char* lds_wave_base) {
-  const uint32_t m0v = __builtin_amdgcn_readfirstlane(
-      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_wave_base);
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-               :: "v"(gptr), "s"(m0v) : "memory");
-}
-
 // LDS: [XCH * 64 rows][128 B]  activation tile (unit u of row r in slot u ^ (r & 7)); XCH = KCH up to
 //      512 input channels: the whole tile stays; beyond that a ring of 8 chunks (chunk kc in slot
 //      kc & 7) that the single pass of the workgroup streams through
@@ -74,7 +66,9 @@ __device__ __forceinline__ void direct_load4(const void* gptr, const unsigned ch
 template <int KCH>
 constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS * 128 + 8 * MAXP * NT * 3 * 64 + 8 * 256; }
 
-template <int MT, int KCH>
+// ACT: a unary activation's table is applied after the clamp (an instantiation of its own: the
+// plain layers keep their code as it is)
+template <int MT, int KCH, bool ACT>
 __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   extern __shared__ __align__(128) unsigned char xs[];
   constexpr int NB = MT * NT;                     // epilogue blocks of a pass
@@ -111,7 +105,7 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   unsigned char* const cst0 = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
   const bool has_res = p.res != nullptr;
   unsigned char* const lutw = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + 8 * (MAXP * NT * 3 * 64) + wave * 256;
-  const bool has_act = p.act_lut != nullptr;        // a unary activation follows the clamp
+  constexpr bool has_act = ACT;                     // a unary activation follows the clamp
 
   int seq = 0;                                   // vector-memory requests issued by this wave
   int mark_r[2] = {0, 0}, mark_c = 0, mark_w[LOOK] = {}, mark_x[KCH] = {};
@@ -485,8 +479,8 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   return lds_bytes(c.KCH) <= 160 * 1024;
 }
 
-template <int MT, int KCH>
-hipError_t launch_t(const ConvParams& p, int splits, hipStream_t st) {
+template <int MT, int KCH, bool ACT>
+hipError_t launch_a(const ConvParams& p, int splits, hipStream_t st) {
   PwpGeom g;
   g.gpr = p.Tin / 16;
   g.G = p.B * g.gpr;
@@ -498,13 +492,18 @@ hipError_t launch_t(const ConvParams& p, int splits, hipStream_t st) {
   g.pps = g.passes / splits;
   static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute((const void*)pw_pipe_kernel<MT, KCH>,
+    const hipError_t e = hipFuncSetAttribute((const void*)pw_pipe_kernel<MT, KCH, ACT>,
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  return launch_kernel(pw_pipe_kernel<MT, KCH>, dim3((unsigned)(8 * g.tiles_per_xcd * g.splits)), dim3(512),
+  return launch_kernel(pw_pipe_kernel<MT, KCH, ACT>, dim3((unsigned)(8 * g.tiles_per_xcd * g.splits)), dim3(512),
                        (size_t)lds_bytes_c<KCH>(), st, p, g);
+}
+
+template <int MT, int KCH>
+hipError_t launch_t(const ConvParams& p, int splits, hipStream_t st) {
+  return p.act_lut ? launch_a<MT, KCH, true>(p, splits, st) : launch_a<MT, KCH, false>(p, splits, st);
 }
 
 }  // namespace

@@ -26,6 +26,14 @@ __device__ __forceinline__ void direct_load16(const void* gptr, const unsigned c
                :: "v"(gptr), "s"(m0v) : "memory");
 }
 
+// One dword per active lane from per-lane global addresses to LDS at lds_wave_base + 4 * lane.
+__device__ __forceinline__ void direct_load4(const void* gptr, const unsigned char* lds_wave_base) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :: "v"(gptr), "s"(m0v) : "memory");
+}
+
 // Global loads whose completion the kernel waits for by hand (wait_vm / tie below).  The
 // compiler does not know that the result is still in flight, so every use has to come after a
 // tie() that follows the wait.

@@ -587,9 +587,9 @@ def test_conformer_shaped_batch16_with_integer_activations():
 
 
 def test_which_activations_run_inside_the_layer_kernel():
-    """Swish after the 512 -> 2048 layers goes through the pointwise kernel's epilogue table; the
-    Swish after the depthwise convolution and the GLU keep the separate in-place pass (the parity
-    test above covers both routes: it runs this very encoder)."""
+    """Swish after the 512 -> 2048 layers and after the depthwise convolutions goes through the
+    producing kernel's epilogue table; the GLU keeps the separate in-place pass (the parity test
+    above covers both routes: it runs this very encoder)."""
     net = W.build_config(5)
     g = GpuNet(net, W.draw_net_params(net, 1))
     kinds = {}
@@ -601,8 +601,8 @@ def test_which_activations_run_inside_the_layer_kernel():
         else:
             assert not g.enc.op_act_fused(i)
     assert kinds[(Q.ACT_SWISH, "pw_pipe", True)] == 17
+    assert kinds[(Q.ACT_SWISH, "dw_pipe", True)] == 17
     assert kinds[(Q.ACT_GLU, "pw_pipe", False)] == 17
-    assert sum(n for (k, kern, fused), n in kinds.items() if k == Q.ACT_SWISH and not fused) == 17
     g.enc.close()
 
 
