@@ -313,7 +313,7 @@ qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, i
 int32_t qasr_encoder_num_ops(const qasr_encoder* e);
 const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i);
 /* 1 if op i's activation (qasr_op.act) is applied inside the layer's own kernel (a unary
- * activation after a layer of the "pw_pipe" family, through a 256-entry table of the
+ * activation after a layer of the "pw_pipe" or "dw_pipe" family, through a 256-entry table of the
  * activation's int8 outputs built at create time), 0 if it runs as the separate in-place pass or
  * the op has none; -1 if i is out of range.  Same bits either way. */
 int32_t qasr_encoder_op_act_fused(const qasr_encoder* e, int32_t i);

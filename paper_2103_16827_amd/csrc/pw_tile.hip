@@ -43,7 +43,6 @@ struct PwtGeom {
   int passes;   // ceil(Cout / (128 * NT))
   int co16n;    // ceil(Cout / 16)
   int tiles, tiles_per_xcd;
-  int dbg;      // tuning: 1 skip activation loads, 2 skip multiply loop, 4 skip epilogue
 };
 
 __device__ __forceinline__ v2i lds_read_tr8(const unsigned char* p) {
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(512) void pw_tile_kernel(ConvParams p, PwtGeom g) {
             stash[(2 * nt + 1) * 64 + lane] = sc[nt];
           }
         }
-        if (active && !(g.dbg & 2)) {
+        if (active) {
           // the activation operand of the next 16-frame group is read from LDS while the current
           // one is multiplied; the scheduling fences keep that order
           const unsigned char* ab = xs + kk * 8192;
@@ -211,7 +210,7 @@ __global__ __launch_bounds__(512) void pw_tile_kernel(ConvParams p, PwtGeom g) {
     }
 
     // ---- epilogue: lane (n, gi) holds frames 16 mt + 4 gi + (0..3) of channel co_w + 16 nt + n
-    if (!active || (g.dbg & 4)) continue;
+    if (!active) continue;
     bool fast = true;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -316,8 +315,6 @@ hipError_t launch_t(const ConvParams& p, hipStream_t st) {
   g.kch = p.Cin / 64;
   g.passes = (p.Cout + 128 * NT - 1) / (128 * NT);
   g.co16n = (p.Cout + 15) / 16;
-  g.dbg = 0;
-  if (const char* e = getenv("QASR_PWT_DBG")) g.dbg = atoi(e);
   const size_t shmem = lds_bytes(p, NT);
   static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
   if (!attr_set) {
