@@ -123,22 +123,25 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     }
     mark_r[par] = seq;
   };
-  // weight stream: chunk q of the flat (pass, chunk) sequence, clamped at its end
-  const int Q = P * KCH;
+  // weight stream: the chunks of the wave's passes in order; past the last pass it goes on with
+  // that pass's first chunks again (in bounds, never multiplied)
   const v4i wrsrc = make_rsrc(p.w, (uint32_t)g.co16n * (uint32_t)KCH * 1024u);
   const uint32_t wlane = (uint32_t)lane * 16;
   v4i wb[LOOK][NT];                               // ring of weight chunks, LOOK chunks ahead of the products
-  auto issue_w = [&](int q, int h) __attribute__((always_inline)) {
-    q = q < Q - 1 ? q : Q - 1;
-    const int ps = q / KCH, kc = q - ps * KCH;
+  // byte offset of chunk 0 of the wave's block nt in pass ps (wave-uniform)
+  auto pass_base = [&](int ps, int nt) __attribute__((always_inline)) {
+    const int co16 = min(((pb + min(ps, P - 1)) * 8 + wave) * NT + nt, g.co16n - 1);
+    return (uint32_t)__builtin_amdgcn_readfirstlane(co16 * (KCH * 1024));
+  };
+  auto issue_w = [&](const uint32_t (&base)[NT], int kc, int h) __attribute__((always_inline)) {
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-      const int co16 = min(((pb + ps) * 8 + wave) * NT + nt, g.co16n - 1);
-      wb[h][nt] = bload16(wrsrc, wlane, (uint32_t)(co16 * KCH + kc) * 1024u);
-    }
+    for (int nt = 0; nt < NT; ++nt) wb[h][nt] = bload16(wrsrc, wlane, base[nt] + (uint32_t)kc * 1024u);
     seq += NT;
     mark_w[h] = seq;
   };
+  uint32_t wcur[NT], wnext[NT];                   // pass_base of the pass being multiplied and of the one after
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) { wcur[nt] = pass_base(0, nt); wnext[nt] = pass_base(1, nt); }
 
   // ---- requests of the start: residual of pass 0, constants of all passes, then the first weight
   // and activation chunks (the first products need only 64 channels)
@@ -171,12 +174,12 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     if (u_ok) direct_load16(xsrc + kc * xstep, xs + 8 * wave * 128 + (kc & 7) * 8192);
     mark_x[kc] = ++seq;
   };
-  issue_w(0, 0);
+  issue_w(wcur, 0, 0);
   issue_x(0);
-  issue_w(1, 1);
+  issue_w(wcur, 1, 1);
   issue_x(1);
 #pragma unroll
-  for (int q = 2; q < LOOK; ++q) issue_w(q, q);
+  for (int q = 2; q < LOOK; ++q) issue_w(wcur, q, q);
 #pragma unroll
   for (int kc = 2; kc < LOOKX && kc < KCH; ++kc) issue_x(kc);
 
@@ -290,6 +293,10 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
     // bias of this pass out of LDS (constants of all passes were requested at the start)
     if (FIRST) wait_vm_dyn(seq - mark_c);
     if (!FIRST) issue_residual(ps, par);      // stage[par] is free: its rows left at the end of pass ps - 1
+    if (!FIRST) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) { wcur[nt] = wnext[nt]; wnext[nt] = pass_base(ps + 1, nt); }
+    }
     {
       const unsigned char* c = cst0 + ps * (NT * 3 * 64) + 4 * n;
 #pragma unroll
@@ -354,7 +361,8 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
           if (!PREV) __builtin_amdgcn_sched_barrier(0);
         }
       }
-      issue_w(ps * KCH + kk + LOOK, h);
+      if (kk + LOOK < KCH) issue_w(wcur, kk + LOOK, h);
+      else issue_w(wnext, kk + LOOK - KCH, h);
     }
     if (PREV) {
 #pragma unroll
