@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import glob
 import os
+import re
 import subprocess
 import sys
 
@@ -33,15 +34,42 @@ def kernels_using_scratch(recs):
     return [r[0] for r in recs if "ScratchSize[bytes/lane]:0" not in r[1:]]
 
 
+def partial_write_hazards(asm_text: str):
+    """Instruction pairs in device assembly where a vector instruction reads a register that the
+    instruction just before it wrote through a byte/word selector (`..._sdwa` with `dst_sel` other
+    than DWORD).  gfx950 needs one instruction in between; the compiler inserts it for its own
+    code but cannot see inside `asm` statements."""
+    ins = []
+    for l in asm_text.splitlines():
+        l = l.strip()
+        if not l or l[0] in ";./" or l.endswith(":"):
+            continue
+        ins.append(l)
+    bad = []
+    for a, b in zip(ins, ins[1:]):
+        if "_sdwa" in a.split()[0] and "dst_sel:" in a and "dst_sel:DWORD" not in a:
+            dst = a.split()[1].rstrip(",")
+            if b.startswith("v_") and re.search(r"\b" + re.escape(dst) + r"\b", b):
+                bad.append((a, b))
+    return bad
+
+
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     bdir = os.path.join(HERE, "_build")
     os.makedirs(bdir, exist_ok=True)
     procs = []
+    sdwa_sources = []
     for src in sources():
         obj = os.path.join(bdir, os.path.basename(src) + ".o")
         cmd = [hipcc, "-x", "hip", "-c", src, "-o", obj] + [f for f in HIPCC_FLAGS if f != "-shared"]
+        with open(src) as f:
+            if "_sdwa" in f.read():              # hand-written partial register writes: device assembly too
+                asm = os.path.join(bdir, os.path.basename(src) + ".gfx950.s")
+                acmd = [hipcc, "-x", "hip", "--cuda-device-only", "-S", src, "-o", asm] + \
+                       [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-Rpass-analysis=kernel-resource-usage")]
+                sdwa_sources.append((src, asm, subprocess.Popen(acmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -81,6 +109,16 @@ def build(verbose: bool = False) -> str:
             f.write(" ".join(r) + "\n")
     # The pipelined kernels count their own vector-memory requests; a spill adds requests nobody
     # counted and moves registers that loads in flight still own.  Such a build must never run.
+    for src, asm, pr in sdwa_sources:
+        out, _ = pr.communicate()
+        if pr.returncode != 0:
+            raise RuntimeError(f"no device assembly for {src}:\n{out}")
+        with open(asm) as f:
+            bad = partial_write_hazards(f.read())
+        if bad:
+            if os.path.exists(LIB):
+                os.remove(LIB)
+            raise RuntimeError(f"{asm}: register read right after a partial write: {bad[0][0]} | {bad[0][1]}")
     spilled = kernels_using_scratch(recs)
     if spilled:
         if os.path.exists(LIB):

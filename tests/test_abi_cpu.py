@@ -295,3 +295,21 @@ def test_build_refuses_kernels_that_spill():
     silent = ["k_without_figure", "VGPRs:12"]
     assert kernels_using_scratch([ok]) == []
     assert kernels_using_scratch([ok, bad, silent]) == ["k_spills", "k_without_figure"]
+
+
+def test_build_checks_reads_after_partial_register_writes():
+    """A vector instruction that reads a register in the slot right after a byte-selected write to it
+    gets stale bytes on this chip; the compiler guards its own code, the build guards the hand-written
+    asm by reading the device assembly."""
+    from paper_2103_16827_amd.build import partial_write_hazards
+    sdwa = "v_ashrrev_i32_sdwa v160, v226, v163 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+    ok = "\n".join(["\t" + sdwa, "\tds_write_b32 v162, v160 offset:2048", "\tv_add_u32_e32 v5, v160, v1"])
+    spaced = "\n".join(["\t" + sdwa, "\t; a comment", "\tv_mfma_i32_16x16x64_i8 v[0:3], v[4:7], v[8:11], v[0:3]", "\t" + sdwa.replace("BYTE_1", "BYTE_2")])
+    bad = "\n".join(["\t" + sdwa, ".Ltmp1:", "\t" + sdwa.replace("BYTE_1", "BYTE_2")])
+    other_reg = "\n".join(["\t" + sdwa, "\tv_add_u32_e32 v5, v16, v1600"])
+    full = "\n".join(["\tv_add_u32_sdwa v7, v1, v2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD", "\tv_add_u32_e32 v5, v7, v1"])
+    assert partial_write_hazards(ok) == []
+    assert partial_write_hazards(spaced) == []
+    assert len(partial_write_hazards(bad)) == 1
+    assert partial_write_hazards(other_reg) == []
+    assert partial_write_hazards(full) == []
