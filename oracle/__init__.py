@@ -19,20 +19,27 @@ _LIB = os.path.join(_HERE, "libqasr_oracle.so")
 _lib = None
 
 
-def build(force: bool = True) -> str:
-    """Compile the oracle with g++ (generic x86-64 code: the .so is also run on another box)."""
-    if force or not os.path.exists(_LIB):
-        cmd = ["g++", "-std=c++17", "-O3", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-               _SRC, "-o", _LIB]
+SANITIZE_FLAGS = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g"]
+
+
+def build(force: bool = True, out: str | None = None, sanitize: bool = False) -> str:
+    """Compile the oracle with g++ (generic x86-64 code: the .so is also run on another box).
+    `sanitize` builds an instrumented copy (-O1, AddressSanitizer and UndefinedBehaviorSanitizer,
+    first report aborts) at `out`; the tests run the pins against it in a child process."""
+    out = out or _LIB
+    if force or not os.path.exists(out):
+        opt = ["-O1"] + SANITIZE_FLAGS if sanitize else ["-O3"]
+        cmd = ["g++", "-std=c++17", *opt, "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", _SRC, "-o", out]
         subprocess.check_call(cmd)
-    return _LIB
+    return out
 
 
 def lib():
     global _lib
     if _lib is None:
-        build(force=False)
-        L = ctypes.CDLL(_LIB)
+        # QASR_ORACLE_SO: load this build instead (the sanitizer tier of the tests sets it)
+        path = os.environ.get("QASR_ORACLE_SO") or build(force=False)
+        L = ctypes.CDLL(path)
         i32, i64, u32, p = ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_void_p
         L.qasr_oracle_num_threads.restype = i32
         L.qasr_oracle_num_threads.argtypes = []
@@ -106,21 +113,31 @@ def conv1d_acc(x, w, bias=None, *, stride=1, dilation=1, pad_left=0, pad_right=0
 
 
 def conv1d_int8(x, w, bias, m, s, residual=None, *, stride=1, dilation=1, pad_left=0, pad_right=0,
-                groups=1, relu=False, Cin=None, x_batch_stride=0, check_overflow=True) -> np.ndarray:
+                groups=1, relu=False, Cin=None, x_batch_stride=0, y_batch_stride=0, y_fill=0,
+                check_overflow=True) -> np.ndarray:
     """One integer layer on host arrays. x int8 [B,Cx,Tin] (Cx >= Cin when a channel-prefix
-    view is read through x_batch_stride), w int8 [Cout,Cin/groups,k], returns int8 [B,Cout,Tout]."""
+    view is read through x_batch_stride), w int8 [Cout,Cin/groups,k], returns int8 [B,Cout,Tout].
+
+    With y_batch_stride (elements, >= Cout*Tout) the output, and the residual operand(s), which share
+    its layout, are [B, y_batch_stride] arrays: item b's [Cout,Tout] block starts at b*y_batch_stride;
+    the bytes between blocks are never read or written (the returned array holds `y_fill` there)."""
     B = x.shape[0]
     Cin = x.shape[1] if Cin is None else Cin
     Tin = x.shape[2]
     Cout, _, k = w.shape
     Tout = out_len(Tin, k, stride, dilation, pad_left, pad_right)
-    y = np.empty((B, Cout, Tout), dtype=np.int8)
+    if y_batch_stride:
+        assert y_batch_stride >= Cout * Tout
+        yshape = (B, y_batch_stride)
+    else:
+        yshape = (B, Cout, Tout)
+    y = np.full(yshape, y_fill, dtype=np.int8)
     if isinstance(residual, (list, tuple)):          # several residual operands: summed, one clamp
         rs = [np.ascontiguousarray(r, dtype=np.int8) for r in residual]
         assert all(r.shape == y.shape for r in rs)
         arr = (ctypes.c_void_p * len(rs))(*[r.ctypes.data for r in rs])
         ovf = lib().qasr_oracle_conv1d_int8_multi(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right,
-                                                  groups, x_batch_stride, 0, 1 if relu else 0,
+                                                  groups, x_batch_stride, y_batch_stride, 1 if relu else 0,
                                                   _ptr(x, np.int8), _ptr(w, np.int8), _ptr(bias, np.int32),
                                                   _ptr(m, np.int32), _ptr(s, np.int32), arr, len(rs),
                                                   _ptr(y, np.int8))
@@ -130,7 +147,7 @@ def conv1d_int8(x, w, bias, m, s, residual=None, *, stride=1, dilation=1, pad_le
     if residual is not None:
         assert residual.shape == y.shape
     ovf = lib().qasr_oracle_conv1d_int8(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right, groups,
-                                        x_batch_stride, 0, 1 if relu else 0,
+                                        x_batch_stride, y_batch_stride, 1 if relu else 0,
                                         _ptr(x, np.int8), _ptr(w, np.int8), _ptr(bias, np.int32),
                                         _ptr(m, np.int32), _ptr(s, np.int32), _ptr(residual, np.int8),
                                         _ptr(y, np.int8))

@@ -265,7 +265,7 @@ inline int64_t iexp_one(int64_t r, const IExp& c) {          // r <= 0
 
 inline int64_t sigmoid_code_one(int q, const IExp& c) {
     const int64_t a = q < 0 ? -int64_t(q) : int64_t(q);
-    const int64_t E = iexp_one(-(a << c.u), c);
+    const int64_t E = iexp_one(-(a * (int64_t(1) << c.u)), c);
     const int64_t E0 = c.q_b * c.q_b + c.q_c;
     const int64_t num = q >= 0 ? E0 : E;
     return (num << 15) / (E0 + E);                             // floor: non-negative operands
@@ -318,10 +318,11 @@ void qasr_oracle_softmax(const int32_t* x, int64_t rows, int64_t L, int u, int64
         const int32_t* xr = x + i * L;
         int64_t mx = xr[0];
         for (int64_t j = 1; j < L; ++j) if (xr[j] > mx) mx = xr[j];
-        int64_t sum = 0;
-        for (int64_t j = 0; j < L; ++j) sum += iexp_one((int64_t(xr[j]) - mx) << c.u, c);
+        const int64_t refine = int64_t(1) << c.u;                 // r_i = (q_i - max) 2^u, a product: the
+        int64_t sum = 0;                                           // difference is negative, never shifted
+        for (int64_t j = 0; j < L; ++j) sum += iexp_one((int64_t(xr[j]) - mx) * refine, c);
         for (int64_t j = 0; j < L; ++j) {
-            const int64_t E = iexp_one((int64_t(xr[j]) - mx) << c.u, c);
+            const int64_t E = iexp_one((int64_t(xr[j]) - mx) * refine, c);
             const int64_t p = (E << 7) / sum;
             y[i * L + j] = int8_t(p > 127 ? 127 : p);
         }

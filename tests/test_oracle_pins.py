@@ -304,33 +304,154 @@ def test_several_residual_operands_are_summed_before_the_one_clamp():
     assert got.tolist() == ref
 
 
+def test_output_batch_stride_places_blocks_and_reads_the_residual_there():
+    """y_batch_stride: item b's [Cout, Tout] block starts at b * stride, in the output and in the
+    residual operand alike; nothing else is read or written.  Checked against the big-integer
+    layer, whose operands are gathered from / scattered to the strided layout here."""
+    B, Cin, Cout, T, k = 3, 3, 5, 17, 3
+    x = _draw(41, (B, Cin, T), -128, 127, np.int8)
+    w = _draw(42, (Cout, Cin, k), -128, 127, np.int8)
+    bias = _draw(43, (Cout,), -300, 300, np.int32)
+    m = _draw(44, (Cout,), 1 << 30, (1 << 31) - 1, np.int32)
+    s = _draw(45, (Cout,), 36, 40, np.int32)
+    Tout = oracle.out_len(T, k, 1, 1, 1, 1)
+    for ybs in (Cout * Tout, Cout * Tout + 4, Cout * Tout + 23):
+        res = _draw(46 + ybs, (B, ybs), -128, 127, np.int8)
+        res_blocks = [[[int(res[b, co * Tout + t]) for t in range(Tout)] for co in range(Cout)] for b in range(B)]
+        for r_flat, r_blocks in ((None, None), (res, res_blocks)):
+            got = oracle.conv1d_int8(x, w, bias, m, s, r_flat, pad_left=1, pad_right=1, y_batch_stride=ybs,
+                                     y_fill=55)
+            ref = py_layer(x.tolist(), w.tolist(), bias.tolist(), m.tolist(), s.tolist(), r_blocks, 1, 1, 1, 1,
+                           False, False)
+            assert got.shape == (B, ybs)
+            assert got[:, : Cout * Tout].reshape(B, Cout, Tout).tolist() == ref
+            assert (got[:, Cout * Tout:] == 55).all()
+    # two residual operands at the stride
+    ybs = Cout * Tout + 9
+    rs = [_draw(60 + i, (B, ybs), -128, 127, np.int8) for i in range(2)]
+    blocks = tuple([[[int(r[b, co * Tout + t]) for t in range(Tout)] for co in range(Cout)] for b in range(B)]
+                   for r in rs)
+    got = oracle.conv1d_int8(x, w, bias, m, s, rs, pad_left=1, pad_right=1, y_batch_stride=ybs, y_fill=-9)
+    ref = py_layer(x.tolist(), w.tolist(), bias.tolist(), m.tolist(), s.tolist(), blocks, 1, 1, 1, 1, False, False)
+    assert got[:, : Cout * Tout].reshape(B, Cout, Tout).tolist() == ref
+    assert (got[:, Cout * Tout:] == -9).all()
+
+
 # ----------------------------------------------------------------------------- a9 wiring on tiny encoders
+LN2_40 = Fraction(6931471805599453094172321214581765680755, 10 ** 40)    # ln 2 to 40 decimals
+
+
+def py_act_constants(S: float, u: int):
+    """The exponential's three integer constants from their defining inequalities, in exact rationals
+    (S is the double the workload drew; the refined step is S / 2^u): the largest integers with
+    q_ln2 S' <= ln 2,  q_b S' <= 1.353,  q_c 0.3585 S'^2 <= 0.344."""
+    Sr = Fraction(S) / 2 ** u
+    q_ln2 = math.floor(LN2_40 / Sr)
+    q_b = math.floor(Fraction(1353, 1000) / Sr)
+    q_c = math.floor(Fraction(344, 1000) / (Fraction(3585, 10000) * Sr * Sr))
+    return q_ln2, q_b, q_c
+
+
+def py_iexp(r: int, q_ln2: int, q_b: int, q_c: int) -> int:
+    """Integer exponential of r <= 0 in unbounded integers: the power of two is split off by a
+    floor division, the second-order polynomial is evaluated on the remainder."""
+    assert r <= 0
+    z = (-r) // q_ln2
+    p = r + z * q_ln2
+    assert -q_ln2 < p <= 0
+    return ((p + q_b) ** 2 + q_c) // 2 ** z
+
+
+def py_sigmoid_code(q: int, u: int, q_ln2: int, q_b: int, q_c: int) -> int:
+    """Sigmoid as the two-way softmax of (x, 0), 15 fractional bits."""
+    E = py_iexp(-abs(q) * 2 ** u, q_ln2, q_b, q_c)
+    E0 = q_b * q_b + q_c
+    return ((E0 if q >= 0 else E) * 2 ** 15) // (E0 + E)
+
+
+def py_act_in_place(a, y):
+    """An op's activation applied to its output [B][C][T] (nested lists) as the encoder does it:
+    sigmoid / swish replace every value; GLU (value = first half of the channels, gate = second
+    half) writes its C/2 channels over the value half and leaves the gate half as it was.  Each
+    result goes back to int8 by the activation's own dyadic rescale (round half up) and clamp."""
+    kind, u, m, s = a["kind"], a["u"], a["m"], a["s"]
+    cst = py_act_constants(a["S"], u)
+    sig = lambda q: py_sigmoid_code(q, u, *cst)
+    out = [[list(row) for row in item] for item in y]
+    for b, item in enumerate(y):
+        C = len(item)
+        n_val = C // 2 if kind == 3 else C
+        for ch in range(n_val):
+            for t, q in enumerate(item[ch]):
+                if kind == 1:
+                    v = sig(q)
+                elif kind == 2:
+                    v = q * sig(q)
+                else:
+                    v = q * sig(item[n_val + ch][t])
+                out[b][ch][t] = min(127, max(-128, py_round_half_up(Fraction(v * m, 2 ** s))))
+    return out
+
+
 def py_encoder(net, params, x):
     slots = {0: x.tolist()}
     for op, p in zip(net.ops, params):
         res = slots[op.res_slot] if op.res_slot >= 0 else None
         if getattr(op, "more_res", None):
             res = (res,) + tuple(slots[r] for r in op.more_res)
-        slots[op.out_slot] = py_layer(
+        y = py_layer(
             slots[op.in_slot], p["w"].tolist(), None if p["bias"] is None else p["bias"].tolist(),
             p["m"].tolist(), p["s"].tolist(), res, op.stride, op.dilation, op.pad_left, op.pad_right,
             op.depthwise, bool(op.flags & 1), Cin=op.Cin)
+        if op.act:
+            y = py_act_in_place(p["act"], y)
+        slots[op.out_slot] = y
     return slots[net.ops[-1].out_slot]
 
 
-@pytest.mark.parametrize("cfg,w_bits", [(0, 8), (1, 8), (2, 8), (3, 8), (4, 8), (6, 8), (7, 8), (1, 6)])
+@pytest.mark.parametrize("cfg,w_bits", [(0, 8), (1, 8), (2, 8), (3, 8), (4, 8), (5, 8), (6, 8), (7, 8), (1, 6)])
 def test_tiny_encoders_match_big_int_composition(cfg, w_bits):
     net = W.tiny_config(cfg)
     for seed in (1, 2):
         # scales chosen for the tiny fan-in so that layers neither saturate nor vanish
         params = W.draw_net_params(net, seed, s_lo=37 - (8 - w_bits), s_hi=38 - (8 - w_bits), bias_mag=300,
                                    w_bits=w_bits)
+        if cfg == 5:
+            # activation outputs at the tiny network's range: swish of codes up to 127 with a
+            # sigmoid code of 15 bits is below 2^22; a ratio near 2^-15 brings it back to int8
+            for p in params:
+                if p.get("act"):
+                    p["act"]["s"] = 45 if p["act"]["kind"] != 1 else 38
         x = W.draw_input(net, seed)
         y, outs = oracle.encoder_forward(net, params, x, keep=True)
         assert y.tolist() == py_encoder(net, params, x)
         assert y.shape == (net.B, net.Cout, net.Tout)
         live = [len(set(o.reshape(-1).tolist())) for o in outs]
         assert min(live) >= 5, live        # no layer collapsed to a constant
+
+
+def test_activation_hook_layouts_against_the_big_int_form():
+    """apply_act on its own: every kind, against the unbounded-integer form, on a tensor that holds
+    every int8 code in both halves; GLU's output sits in the first half, the gate half is unchanged;
+    the exponential's constants equal the ones fixed by their defining inequalities."""
+    B, C, T = 2, 6, 256
+    codes = np.arange(-128, 128, dtype=np.int8)
+    y = np.empty((B, C, T), dtype=np.int8)
+    for b in range(B):
+        for ch in range(C):
+            y[b, ch] = np.roll(codes, 37 * ch + 11 * b)
+    for kind, s in ((1, 38), (2, 45), (3, 45)):
+        for S, u in ((0.05, 8), (6.0 / 127.0, 8), (0.02, 4)):
+            a = {"kind": kind, "S": S, "u": u, "m": (1 << 30) + 123456789, "s": s}
+            c = oracle.iexp_constants(S, u)
+            assert (c["q_ln2"], c["q_b"], c["q_c"]) == py_act_constants(S, u)
+            got = oracle.apply_act(a, y)
+            assert got.shape == y.shape and got.dtype == np.int8
+            assert got.tolist() == py_act_in_place(a, y.tolist()), (kind, S, u)
+            if kind == 3:
+                assert np.array_equal(got[:, C // 2:], y[:, C // 2:])
+                assert not np.array_equal(got[:, : C // 2], y[:, : C // 2])
+            assert len(set(got[:, : (C // 2 if kind == 3 else C)].reshape(-1).tolist())) > 20
 
 
 def test_config0_oracle_is_not_degenerate():
