@@ -72,8 +72,10 @@ typedef struct {
   uint32_t flags;                          /* QASR_FLAG_*                                             */
 } qasr_conv1d_desc;
 
-/* Tout = floor((Tin + pad_left + pad_right - dilation*(k-1) - 1) / stride) + 1, or a negative
- * qasr_status if the descriptor is invalid (NULL, sizes < 1, or no output frame). */
+/* Output length of the integer convolution of Sec. 2.2 under this descriptor (the usual Conv1d
+ * geometry with implicit zeros, the zero-point of Eq. 1's symmetric quantiser):
+ * Tout = floor((Tin + pad_left + pad_right - dilation*(k-1) - 1) / stride) + 1, or a negative
+ * qasr_status if the descriptor is invalid (NULL, sizes < 1, or no output frame).  HOST only. */
 int32_t qasr_conv1d_out_len(const qasr_conv1d_desc* d);
 
 /* One integer layer as defined at the top of this file (Sec. 2.2: integer convolution, folded
@@ -91,7 +93,6 @@ qasr_status qasr_conv1d_int8(const qasr_conv1d_desc* d, const int8_t* x, const i
                              const int32_t* bias, const int32_t* m, const int32_t* s,
                              const int8_t* residual, int8_t* y, void* stream);
 
-/* Size in bytes of the packed form of a layer's weights (0 on an invalid descriptor). */
 /* The layer with several residual operands (the dense-residual wiring of the Jasper family named
  * in Sec. 3: a block receives the projected inputs of all earlier blocks).  Reading: every operand
  * is int8 at the output scale and shaped like y (same batch stride); all are added to the
@@ -104,6 +105,7 @@ qasr_status qasr_conv1d_int8_multi(const qasr_conv1d_desc* d, const int8_t* x, c
                                    const int8_t* const* residuals, int32_t n_res, int8_t* y,
                                    void* stream);
 
+/* Size in bytes of the packed form of a layer's weights (0 on an invalid descriptor).  HOST only. */
 size_t qasr_packed_weight_bytes(const qasr_conv1d_desc* d);
 
 /* Re-orders w [Cout,Cin,k] of a groups == 1 layer with Cin % 64 == 0 into the matrix-core operand
@@ -116,17 +118,16 @@ size_t qasr_packed_weight_bytes(const qasr_conv1d_desc* d);
 qasr_status qasr_pack_weights(const qasr_conv1d_desc* d, const int8_t* w, int8_t* w_packed,
                               void* stream);
 
-/* The layer epilogue alone (bias, dyadic rescale, residual, clamp) on int32 accumulators:
+/* The layer epilogue alone on int32 accumulators: what Sec. 2.2 leaves after the integer convolution
+ * itself (the folded BatchNorm's bias, the return to int8 at the static output scale of Sec. 2.1 as
+ * a dyadic rescale, the residual add, integer ReLU / saturation), i.e. the last four lines of the
+ * layer definition at the top of this file with A = acc + bias:
  *   acc [B,C,T] int32 device; bias/m/s [C]; residual, y [B,C,T] int8 device (contiguous).
  * flags: QASR_FLAG_RELU only.  Asynchronous on `stream`. */
 qasr_status qasr_requant(const int32_t* acc, int32_t B, int32_t C, int32_t T,
                          const int32_t* bias, const int32_t* m, const int32_t* s,
                          const int8_t* residual, uint32_t flags, int8_t* y, void* stream);
 
-/* An encoder is a flat list of layers over numbered activation slots (the evaluated models of
- * Sec. 3 are such lists: QuartzNet, Jasper, Conformer-shaped linear layers).  Slot 0 is the
- * network input `x`; the last op's out_slot is the network output `y`; every other slot
- * lives in the caller's workspace. */
 /* Quantiser at the entrance of the path (the paper's Eq. 1 with b = 8):
  *   q[i] = Int(clip(x[i], -alpha, alpha) / S),  S = alpha / 127,  q in [-127, 127].
  * x: n float32 features (device), q: n int8 codes (device), any alignment, same element order
@@ -178,7 +179,9 @@ qasr_status qasr_fold_bn_quantize(const float* w, const float* conv_bias, const 
                                   int32_t* bad_count, void* stream);
 
 /* Integer-only non-linear activations (Sec. 2.2, last sentence; Sec. 3, first paragraph: Sigmoid,
- * Softmax and Swish through second-order polynomials, no floating point executed).  The paper
+ * Softmax and Swish through second-order polynomials; every result is defined and computed in
+ * integers: where a kernel uses a single-precision reciprocal it is only an estimate of a quotient
+ * that an exact integer remainder check then corrects).  The paper
  * refers to the integer-only Transformer work it cites for the procedure; as restated here:
  *
  *   exp(x), x <= 0:  x = -z ln2 + p, p in (-ln2, 0], exp(p) ~ 0.3585 (p + 1.353)^2 + 0.344.
@@ -230,6 +233,10 @@ qasr_status qasr_act_int8(const qasr_act* a, const int8_t* x, int32_t B, int32_t
 qasr_status qasr_softmax_int32(const qasr_iexp* e, const int32_t* x, int64_t rows, int32_t L,
                                int8_t* y, void* stream);
 
+/* An encoder is a flat list of layers over numbered activation slots (the evaluated models of
+ * Sec. 3 are such lists: QuartzNet, Jasper, Conformer-shaped linear layers).  Slot 0 is the
+ * network input `x`; the last op's out_slot is the network output `y`; every other slot
+ * lives in the caller's workspace. */
 typedef struct {
   qasr_conv1d_desc d;        /* d.x_batch_stride / y_batch_stride as for qasr_conv1d_int8; flags
                                 must not contain QASR_FLAG_W_PACKED (create packs by itself)         */
@@ -261,7 +268,8 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
                                 qasr_encoder** out);
 
 /* Bytes of workspace qasr_encoder_forward needs (all slots except the input and the output,
- * each rounded up to 256 bytes). */
+ * each rounded up to 256 bytes).  Known at create time because every shape and scale of the
+ * integer model is static (Sec. 2.1: static quantisation, nothing is sized at inference).  HOST only. */
 size_t qasr_encoder_workspace_bytes(const qasr_encoder* e);
 
 /* Runs every op in order on `stream`.  x: [B,Cin,Tin] of the first op's descriptor; y: output
@@ -307,9 +315,8 @@ qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, i
                                        float* op_ms);
 
 /* Number of ops, and the name of the kernel family op i is dispatched to (depthwise:
- * "dw_pipe", "dw_mfma"; pointwise: "pw_pipe", "pw_stream", "pw_tile", "pw_mfma"; dense:
- * "conv_pipe", "gemm_mfma";
- * any shape: "conv_generic"; static storage, NULL if i is out of range). */
+ * "dw_pipe", "dw_mfma"; pointwise: "pw_pipe", "pw_tile"; dense and any other pointwise shape:
+ * "conv_pipe", "gemm_mfma"; any shape: "conv_generic"; static storage, NULL if i is out of range). */
 int32_t qasr_encoder_num_ops(const qasr_encoder* e);
 const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i);
 /* 1 if op i's activation (qasr_op.act) is applied inside the layer's own kernel (a unary
@@ -324,6 +331,11 @@ void qasr_encoder_destroy(qasr_encoder* e);
 const char* qasr_conv1d_kernel_name(const qasr_conv1d_desc* d);
 
 const char* qasr_status_string(qasr_status st);
+
+/* The library reads its tuning overrides (environment variables QASR_*: forced tile shapes, kernel
+ * families switched off; for sweeps and tests, never needed for correct results) once, at first
+ * use.  This reads them again.  HOST only; not to be called while another thread launches. */
+void qasr_tuning_reload(void);
 
 /* Name of the HIP error behind the calling thread's most recent QASR_ERR_HIP ("hipSuccess" if
  * there was none).  Static storage. */

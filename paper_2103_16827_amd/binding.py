@@ -130,6 +130,8 @@ def lib():
         L.qasr_last_hip_error.argtypes = []
         L.qasr_status_string.restype = ctypes.c_char_p
         L.qasr_status_string.argtypes = [_i32]
+        L.qasr_tuning_reload.restype = None
+        L.qasr_tuning_reload.argtypes = []
         _lib = L
     return _lib
 
@@ -156,6 +158,11 @@ def make_desc(B, Cin, Cout, Tin, k=1, stride=1, dilation=1, pad_left=0, pad_righ
               x_batch_stride=0, y_batch_stride=0, flags=0) -> ConvDesc:
     return ConvDesc(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right, groups,
                     x_batch_stride, y_batch_stride, flags)
+
+
+def tuning_reload() -> None:
+    """qasr_tuning_reload: read the QASR_* tuning environment variables again."""
+    lib().qasr_tuning_reload()
 
 
 def conv1d_out_len(d: ConvDesc) -> int:

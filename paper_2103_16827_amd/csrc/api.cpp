@@ -2,6 +2,7 @@
 // encoder executor (a flat op list over activation slots).  See include/qasr.h.
 #include "../../include/qasr.h"
 #include "kernels.hpp"
+#include "tuning.hpp"
 
 #include <cmath>
 #include <new>
@@ -69,7 +70,7 @@ ConvParams make_params(const qasr_conv1d_desc* d, const int8_t* x, const int8_t*
   return p;
 }
 
-enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwMfma, PwTile, PwStream, PwPipe, ConvPipe };
+enum class Kernel { Generic, DwMfma, DwPipe, GemmMfma, PwTile, PwPipe, ConvPipe };
 
 Kernel pick_kernel(const ConvParams& p) {
   if (p.n_res_more > 0)      // dense-residual layers: the two kernels whose epilogue adds several operands
@@ -79,9 +80,7 @@ Kernel pick_kernel(const ConvParams& p) {
     return qasr::dw_mfma_supported(p) ? Kernel::DwMfma : Kernel::Generic;
   }
   if (qasr::pw_pipe_supported(p)) return Kernel::PwPipe;
-  if (qasr::pw_stream_supported(p)) return Kernel::PwStream;
   if (qasr::pw_tile_supported(p)) return Kernel::PwTile;
-  if (qasr::pw_mfma_supported(p)) return Kernel::PwMfma;
   if (qasr::conv_pipe_supported(p)) return Kernel::ConvPipe;
   if (qasr::gemm_mfma_supported(p)) return Kernel::GemmMfma;
   return Kernel::Generic;
@@ -95,9 +94,7 @@ const char* kernel_name(Kernel k) {
     case Kernel::DwMfma: return "dw_mfma";
     case Kernel::DwPipe: return "dw_pipe";
     case Kernel::GemmMfma: return "gemm_mfma";
-    case Kernel::PwMfma: return "pw_mfma";
     case Kernel::PwTile: return "pw_tile";
-    case Kernel::PwStream: return "pw_stream";
     case Kernel::PwPipe: return "pw_pipe";
     case Kernel::ConvPipe: return "conv_pipe";
     default: return "conv_generic";
@@ -110,9 +107,7 @@ qasr_status launch_with(Kernel k, const ConvParams& p, hipStream_t st) {
     case Kernel::DwMfma: e = qasr::launch_dw_mfma(p, st); break;
     case Kernel::DwPipe: e = qasr::launch_dw_pipe(p, st); break;
     case Kernel::GemmMfma: e = qasr::launch_gemm_mfma(p, st); break;
-    case Kernel::PwMfma: e = qasr::launch_pw_mfma(p, st); break;
     case Kernel::PwTile: e = qasr::launch_pw_tile(p, st); break;
-    case Kernel::PwStream: e = qasr::launch_pw_stream(p, st); break;
     case Kernel::PwPipe: e = qasr::launch_pw_pipe(p, st); break;
     case Kernel::ConvPipe: e = qasr::launch_conv_pipe(p, st); break;
     default: e = qasr::launch_conv_generic(p, st); break;
@@ -639,6 +634,8 @@ void qasr_encoder_destroy(qasr_encoder* e) {
   if (e->packed) (void)hipFree(e->packed);
   delete e;
 }
+
+void qasr_tuning_reload(void) { qasr::tuning_reload(); }
 
 const char* qasr_last_hip_error(void) { return hipGetErrorName(g_last_hip); }
 

@@ -23,6 +23,7 @@
 // what bounds the kernel.  Small layers are bound by the number of workgroups instead: the tile
 // (16 MT frames x 64 NT channels per wave) is chosen per layer by a small occupancy model.
 #include "kernels.hpp"
+#include "tuning.hpp"
 
 #include <cmath>
 #include <cstdio>
@@ -262,7 +263,7 @@ double step_cycles(int MT, int NT, int64_t blocks) {
 }
 
 bool pick(const ConvParams& p, int& MT, int& NT) {
-  if (getenv("QASR_NO_CONV_PIPE")) return false;          // tuning: fall through to gemm_mfma
+  if (tuning().no_conv_pipe) return false;                // tuning: fall through to gemm_mfma
   if (p.depthwise || p.Cin % 64 != 0 || !p.w_packed || p.k < 2) return false;
   if (p.Cout < 64) return false;
   if (p.Tin % 4 != 0 || p.Tout % 4 != 0 || p.xbs % 4 != 0 || p.ybs % 4 != 0) return false;
@@ -274,8 +275,7 @@ bool pick(const ConvParams& p, int& MT, int& NT) {
   if ((int64_t)p.k * ((p.Cout + 15) / 16) * (p.Cin / 64) * 1024 > 0x7fffffffLL) return false;
   // frames per tile: 96 or 64 (128 would need all 256 registers and leave one wave per SIMD:
   // measured slower than 96 with two); channels per tile: 256 or 128
-  int force_mt = 0, force_nt = 0;
-  if (const char* e = getenv("QASR_CP_TILE")) sscanf(e, "%d,%d", &force_mt, &force_nt);   // tuning
+  const int force_mt = tuning().cp_mt, force_nt = tuning().cp_nt;   // tuning
   static const int MTs[] = {8, 7, 6, 5, 4}, NTs[] = {4, 2};
   double best = 1e300;
   bool found = false;

@@ -17,6 +17,7 @@
 // 16-frame groups of all its strips as one flat column space so that MFMA tiles stay full
 // across row ends.
 #include "kernels.hpp"
+#include "tuning.hpp"
 
 #include <cstdlib>
 #include <type_traits>
@@ -226,8 +227,8 @@ bool geometry(const ConvParams& p, DwGeom& g, int& KC) {
       if (score > best + 1e-9) { best = score; g.R = R; }
     }
   }
-  if (const char* e = getenv("QASR_DW_R")) {             // tuning override: strips per wave
-    const int R = atoi(e);
+  {                                                      // tuning override: strips per wave
+    const int R = tuning().dw_r;
     if (g.nseg == 1 && (R == 1 || R == 2 || R == 4 || R == 8) && R * g.NI <= 8 &&
         (int64_t)R * p.ybs < 0x7fffffffLL)
       g.R = R;

@@ -29,6 +29,7 @@
 // 4-byte aligned outputs and no residual operand; everything else is served by dw_mfma.hip.
 #include "kernels.hpp"
 #include "vmem.hpp"
+#include "tuning.hpp"
 
 #include <cstdio>
 #include <cstdlib>
@@ -293,10 +294,9 @@ bool plan(const ConvParams& p, DwpGeom& g, Plan& pl) {
   pl.S = 1;
   while ((int64_t)p.Cout * pl.S < 1024 && rows / ((int64_t)4 * (pl.S * 2)) >= 3) pl.S *= 2;
   if (pl.NI == 1 && 2 * g.G <= 16 * kMaxTiles && rows / ((int64_t)4 * pl.S) >= 12) pl.R = 2;
-  if (const char* e = getenv("QASR_DWP")) {              // tuning override: "R,S"
-    int r = 0, s = 0;
-    if (sscanf(e, "%d,%d", &r, &s) == 2 && (r == 1 || (r == 2 && pl.NI == 1 && 2 * g.G <= 16 * kMaxTiles)) &&
-        s >= 1 && s <= 64) {
+  {                                                      // tuning override: "R,S"
+    const int r = tuning().dwp_r, s = tuning().dwp_s;
+    if ((r == 1 || (r == 2 && pl.NI == 1 && 2 * g.G <= 16 * kMaxTiles)) && s >= 1 && s <= 64) {
       pl.R = r; pl.S = s;
     }
   }

@@ -25,10 +25,6 @@ hipError_t launch_dw_mfma(const ConvParams& p, hipStream_t st);
 bool gemm_mfma_supported(const ConvParams& p);
 hipError_t launch_gemm_mfma(const ConvParams& p, hipStream_t st);
 
-// Pointwise convolution (k = 1) with LDS transpose reads; needs 16-byte aligned frame rows.
-bool pw_mfma_supported(const ConvParams& p);
-hipError_t launch_pw_mfma(const ConvParams& p, hipStream_t st);
-
 // Depthwise convolution, same arithmetic, software-pipelined over the batch (reads and writes of
 // HBM overlap); needs aligned rows, no residual and enough rows per wave to pipeline.
 bool dw_pipe_supported(const ConvParams& p);
@@ -38,12 +34,6 @@ hipError_t launch_dw_pipe(const ConvParams& p, hipStream_t st);
 // needs packed weights, rows that are a multiple of 16 frames and Cin <= 1024.
 bool pw_tile_supported(const ConvParams& p);
 hipError_t launch_pw_tile(const ConvParams& p, hipStream_t st);
-
-// Pointwise convolution (k = 1), weights stationary in registers, activations streamed through LDS
-// by persistent workgroups; needs packed weights, rows that are a multiple of 16 frames,
-// Cin in {256, 512, 2048} and at least 64 output channels per 16-channel tile column.
-bool pw_stream_supported(const ConvParams& p);
-hipError_t launch_pw_stream(const ConvParams& p, hipStream_t st);
 
 // Pointwise convolution (k = 1), activation tile stationary in LDS, output channels in passes of
 // 256 whose epilogues run in between the matrix products of the following pass; needs packed

@@ -26,6 +26,7 @@
 // brought there by direct loads before the multiply loop starts, the epilogue adds it and puts the
 // packed int8 results back in place, and the rows leave as 16-byte stores, 8 lanes per row.
 #include "kernels.hpp"
+#include "tuning.hpp"
 #include "vmem.hpp"
 
 #include <cstdlib>
@@ -300,8 +301,8 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
     const double cost = (double)((tiles + cus - 1) / cus) * (MT + 1.0);
     if (cost < best - 1e-9) { best = cost; c.MT = MT; }
   }
-  if (const char* e = getenv("QASR_PWT_MT")) {          // tuning override
-    const int mt = atoi(e);
+  {                                                     // tuning override
+    const int mt = tuning().pwt_mt;
     if (mt >= 4 && mt <= 8) c.MT = mt;
   }
   return true;
@@ -316,13 +317,9 @@ hipError_t launch_t(const ConvParams& p, hipStream_t st) {
   g.passes = (p.Cout + 128 * NT - 1) / (128 * NT);
   g.co16n = (p.Cout + 15) / 16;
   const size_t shmem = lds_bytes(p, NT);
-  static bool attr_set = false;   // raise the dynamic LDS limit once per instantiation
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute((const void*)pw_tile_kernel<MT, NT>,
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_raised{0};   // per instantiation, a bit per device
+  if (const hipError_t e = ensure_max_dynamic_lds((const void*)pw_tile_kernel<MT, NT>, lds_raised); e != hipSuccess)
+    return e;
   g.tiles = (g.G + MT - 1) / MT;
   g.tiles_per_xcd = (g.tiles + 7) / 8;
   return launch_kernel(pw_tile_kernel<MT, NT>, dim3((unsigned)(8 * g.tiles_per_xcd)), dim3(512), shmem, st, p, g);

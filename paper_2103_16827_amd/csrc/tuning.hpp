@@ -1,0 +1,27 @@
+// Tuning overrides of the kernel choices, read from the environment ONCE (at first use) instead of
+// on every launch; tuning_reload() reads them again (tests and sweeps that change the environment
+// of a running process call it through qasr_tuning_reload).  0 / false = no override.
+//   QASR_NO_PW_PIPE, QASR_NO_CONV_PIPE      fall through to the next kernel family
+//   QASR_PWP_MT, QASR_PWP_SPLIT             pw_pipe: groups per tile, workgroups per tile
+//   QASR_DWP = "R,S"                        dw_pipe: rows per iteration, batch splits
+//   QASR_DW_R                               dw_mfma: strips per wave
+//   QASR_CP_TILE = "MT,NT"                  conv_pipe: tile
+//   QASR_PWT_MT                             pw_tile: groups per tile
+//   QASR_NO_TEAM                            encoder: no persistent team kernel, one launch per op
+#pragma once
+
+namespace qasr {
+
+struct Tuning {
+  bool no_pw_pipe = false, no_conv_pipe = false, no_team = false;
+  int pwp_mt = 0, pwp_split = 0;
+  int dwp_r = 0, dwp_s = 0;
+  int dw_r = 0;
+  int cp_mt = 0, cp_nt = 0;
+  int pwt_mt = 0;
+};
+
+const Tuning& tuning();
+void tuning_reload();
+
+}  // namespace qasr

@@ -19,11 +19,29 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 
 // 64 lanes x 16 bytes from per-lane global addresses to LDS at lds_wave_base + 16 * lane
 // (lds_wave_base must be wave-uniform).  Completion is counted by vmcnt.
+// (m0 is written here and cannot be named as clobbered: to the compiler it is a reserved register,
+// it refuses to honour such a clobber.  The kernels that use these loads index no register
+// dynamically and send no messages, the compiler's own uses of m0; every such load sets m0 itself.)
 __device__ __forceinline__ void direct_load16(const void* gptr, const unsigned char* lds_wave_base) {
   const uint32_t m0v = __builtin_amdgcn_readfirstlane(
       (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_wave_base);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :: "v"(gptr), "s"(m0v) : "memory");
+}
+// The same load at device scope (sc1): it never hits in the vector cache of the compute unit, so it
+// sees what other workgroups of the same XCD have stored (and the XCD's L2 has acknowledged) earlier
+// in the same kernel.  A vector-cache invalidate that spares the L2 does not exist on this chip:
+// `buffer_inv sc0` leaves stale lines in place and `buffer_inv sc1` also drops the L2's contents (15 us).
+__device__ __forceinline__ void direct_load16_dev(const void* gptr, const unsigned char* lds_wave_base) {
+  const uint32_t m0v = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_wave_base);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off sc1"
+               :: "v"(gptr), "s"(m0v) : "memory");
+}
+template <bool DEV>
+__device__ __forceinline__ void direct_load16_scope(const void* gptr, const unsigned char* lds_wave_base) {
+  if constexpr (DEV) direct_load16_dev(gptr, lds_wave_base);
+  else direct_load16(gptr, lds_wave_base);
 }
 
 // One dword per active lane from per-lane global addresses to LDS at lds_wave_base + 4 * lane.

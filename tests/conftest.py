@@ -26,3 +26,19 @@ def read_golden(name):
 @pytest.fixture(scope="session")
 def golden():
     return read_golden
+
+
+@pytest.fixture
+def tuning_env(monkeypatch):
+    """Sets QASR_* tuning variables for one test.  The library reads them once, at first use, so it
+    is told to read them again after every change and once more when the test's environment is
+    restored."""
+    import paper_2103_16827_amd as Q
+
+    def set_(name, value):
+        monkeypatch.setenv(name, value)
+        Q.tuning_reload()
+
+    yield set_
+    monkeypatch.undo()
+    Q.tuning_reload()

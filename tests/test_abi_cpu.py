@@ -261,7 +261,7 @@ def test_kernel_dispatch_names():
     assert Q.conv1d_kernel_name(make_desc(32, 512, 512, 800, k=63, pad_left=31, pad_right=31, groups=512)) == "dw_pipe"
     assert Q.conv1d_kernel_name(make_desc(1, 512, 512, 800, k=63, pad_left=31, pad_right=31, groups=512)) == "dw_mfma"
     assert Q.conv1d_kernel_name(make_desc(32, 512, 512, 800, flags=Q.FLAG_W_PACKED)) == "pw_pipe"
-    assert Q.conv1d_kernel_name(make_desc(32, 256, 128, 800, flags=Q.FLAG_W_PACKED)) == "pw_stream"
+    assert Q.conv1d_kernel_name(make_desc(32, 256, 128, 800, flags=Q.FLAG_W_PACKED)) == "pw_tile"
     assert Q.conv1d_kernel_name(make_desc(32, 1024, 29, 800, flags=Q.FLAG_W_PACKED)) == "pw_tile"
     assert Q.conv1d_kernel_name(make_desc(1, 5, 5, 9, k=3, stride=2, groups=5)) == "conv_generic"
     assert Q.conv1d_kernel_name(make_desc(1, 5, 7, 9, k=3)) == "conv_generic"

@@ -81,14 +81,18 @@ def layer_case(name, B, Cin, Cout, T, k=1, stride=1, dil=1, pad=None, dw=False, 
     return op, p, x, r, packed
 
 
-def run_layer_case(case):
+def run_layer_case(case, ybs_extra=None):
+    """ybs_extra: None = dense output; n = output (and residual) batch stride Cout*Tout + n."""
     op, p, x, r, packed = case
     B = x.shape[0]
-    kern = Q.conv1d_kernel_name(desc_of(op, B, Q.FLAG_W_PACKED if packed else 0))
+    ybs = 0 if ybs_extra is None else op.Cout * op.Tout + ybs_extra
+    d = desc_of(op, B, Q.FLAG_W_PACKED if packed else 0)
+    d.y_batch_stride = ybs
+    kern = Q.conv1d_kernel_name(d)
     say(f"layer {op.name} B={B} Cin={op.Cin} Cout={op.Cout} T={op.Tin} k={op.k} s={op.stride} d={op.dilation} "
-        f"pad=({op.pad_left},{op.pad_right}) dw={op.depthwise} packed={packed} -> {kern}")
+        f"pad=({op.pad_left},{op.pad_right}) dw={op.depthwise} packed={packed} ybs={ybs} -> {kern}")
     ref = oracle.run_op(op, p, x, r)
-    got = gpu_layer(op, B, p, x, r, packed=packed)
+    got = gpu_layer(op, B, p, x, r, packed=packed, ybs=ybs)
     bad = np.argwhere(got != ref)
     assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[tuple(bad[0])]} want {ref[tuple(bad[0])]}"
     return kern
@@ -163,6 +167,45 @@ def test_real_shape_layers(kw):
     run_layer_case(layer_case(**kw))
 
 
+# Output (and residual) batch strides larger than Cout*Tout, for every kernel family: a multiple of
+# 16 bytes beyond the dense stride (the pipelined kernels keep serving the layer) and an odd
+# multiple of 4 (their alignment conditions send the layer to another kernel).  gpu_layer checks that
+# the gap bytes between the batch items' blocks and the canary bands around the buffer stay untouched.
+STRIDED = [
+    dict(name="ybs_dw_pipe", B=13, Cin=24, Cout=24, T=800, k=33, dw=True, bias=False),
+    dict(name="ybs_dw_mfma_res", B=3, Cin=70, Cout=70, T=1037, k=39, dw=True, res=True),
+    dict(name="ybs_dw_mfma", B=2, Cin=256, Cout=256, T=800, k=51, dw=True, bias=False, relu=False),
+    dict(name="ybs_pw_pipe_res", B=3, Cin=512, Cout=512, T=336, res=True, packed=True),
+    dict(name="ybs_pw_pipe", B=2, Cin=256, Cout=768, T=800, packed=True),
+    dict(name="ybs_pw_pipe_streamed_res", B=2, Cin=2048, Cout=512, T=400, res=True, packed=True),
+    dict(name="ybs_pw_tile_res", B=2, Cin=1024, Cout=29, T=800, relu=False, res=True, packed=True),
+    dict(name="ybs_pw_tile_narrow", B=2, Cin=256, Cout=128, T=320, res=True, packed=True),
+    dict(name="ybs_gemm_mfma_wide_res", B=2, Cin=1280, Cout=72, T=320, res=True, packed=True),
+    dict(name="ybs_conv_pipe_res", B=2, Cin=128, Cout=328, T=428, k=11, packed=True, res=True),
+    dict(name="ybs_conv_pipe_s2", B=2, Cin=64, Cout=256, T=1600, k=33, stride=2, pad=(16, 16), packed=True),
+    dict(name="ybs_gemm_mfma_res", B=3, Cin=192, Cout=200, T=333, res=True, packed=True),
+    dict(name="ybs_generic_res", B=2, Cin=3, Cout=5, T=17, k=3, stride=2, dil=2, pad=(2, 1), res=True, relu=False),
+]
+
+
+@pytest.mark.parametrize("extra", [16, 4, 4096])
+@pytest.mark.parametrize("kw", STRIDED, ids=[c["name"] for c in STRIDED])
+def test_output_batch_stride(kw, extra):
+    run_layer_case(layer_case(**kw), ybs_extra=extra)
+
+
+def test_output_batch_stride_cases_cover_every_kernel_family():
+    seen = set()
+    for kw in STRIDED:
+        op, p, x, r, packed = layer_case(**kw)
+        for extra in (16, 4):
+            d = desc_of(op, x.shape[0], Q.FLAG_W_PACKED if packed else 0)
+            d.y_batch_stride = op.Cout * op.Tout + extra
+            seen.add(Q.conv1d_kernel_name(d))
+    say(f"kernels reached with a padded output stride: {sorted(seen)}")
+    assert {"dw_pipe", "dw_mfma", "pw_pipe", "pw_tile", "conv_pipe", "gemm_mfma", "conv_generic"} <= seen, seen
+
+
 # The pipelined depthwise kernel (batches of 12 and more): one and two 64-chunk slices per row,
 # short rows that share a 256-frame tile, long rows, every rescale form, odd batch sizes.
 DWPIPE = [
@@ -182,9 +225,9 @@ def test_pipelined_depthwise_layers(kw):
 
 
 @pytest.mark.parametrize("rs", ["2,1", "1,1", "1,2", "2,2"])
-def test_pipelined_depthwise_row_and_split_choices(rs, monkeypatch):
+def test_pipelined_depthwise_row_and_split_choices(rs, tuning_env):
     """Rows per iteration and batch splits other than the ones the heuristic picks."""
-    monkeypatch.setenv("QASR_DWP", rs)
+    tuning_env("QASR_DWP", rs)
     assert run_layer_case(layer_case(name="dwp_rs", B=48, Cin=8, Cout=8, T=400, k=51, dw=True)) == "dw_pipe"
 
 
@@ -199,10 +242,10 @@ CP_SHAPES = [
 
 @pytest.mark.parametrize("tile", CP_TILES)
 @pytest.mark.parametrize("kw", CP_SHAPES, ids=[c["name"] for c in CP_SHAPES])
-def test_pipelined_dense_tile_choices(kw, tile, monkeypatch):
+def test_pipelined_dense_tile_choices(kw, tile, tuning_env):
     if kw.get("stride", 1) > 1 and tile.startswith("8"):
         pytest.skip("128 output frames at stride 2 exceed the kernel's 256 LDS rows")
-    monkeypatch.setenv("QASR_CP_TILE", tile)
+    tuning_env("QASR_CP_TILE", tile)
     assert run_layer_case(layer_case(**kw)) == "conv_pipe"
 
 
@@ -211,8 +254,8 @@ DENSE = [c for c in REAL if c.get("k", 1) > 1 and not c.get("dw") and c.get("pac
 
 
 @pytest.mark.parametrize("kw", DENSE, ids=[c["name"] for c in DENSE])
-def test_dense_layers_through_the_unpipelined_kernel(kw, monkeypatch):
-    monkeypatch.setenv("QASR_NO_CONV_PIPE", "1")
+def test_dense_layers_through_the_unpipelined_kernel(kw, tuning_env):
+    tuning_env("QASR_NO_CONV_PIPE", "1")
     assert run_layer_case(layer_case(**kw)) in ("gemm_mfma", "conv_generic")
 
 
@@ -243,7 +286,7 @@ def test_pipelined_pointwise_layers(kw):
 
 @pytest.mark.parametrize("split", [1, 2, 4, 8])
 @pytest.mark.parametrize("case", ["2048_res_mixed", "1024_norelu_ragged_rows"])
-def test_pipelined_pointwise_output_channel_splits(case, split, monkeypatch):
+def test_pipelined_pointwise_output_channel_splits(case, split, tuning_env):
     """Several workgroups per frame tile, each with its own run of 256-channel passes (what the
     heuristic chooses when the tiles alone do not fill the chip), forced here."""
     if case == "2048_res_mixed":
@@ -253,7 +296,7 @@ def test_pipelined_pointwise_output_channel_splits(case, split, monkeypatch):
         if split == 8:
             pytest.skip("4 passes")
         op, p, x, r, packed = layer_case(name="pipe_split", B=3, Cin=256, Cout=1024, T=336, relu=False, packed=True)
-    monkeypatch.setenv("QASR_PWP_SPLIT", str(split))
+    tuning_env("QASR_PWP_SPLIT", str(split))
     assert run_layer_case((op, p, x, r, packed)) == "pw_pipe"
 
 
@@ -279,16 +322,11 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
                 want = "dw_pipe" if net.B >= 12 else "dw_mfma"
             elif o.k == 1 and o.Tin % 16 == 0:
                 # pipelined / weights-in-registers kernels for the instantiated widths, else the tile kernels
-                nt = {4: 4 if o.Cout > 256 else 2, 8: 4}.get(o.Cin // 64 if o.Cin % 64 == 0 else 0)
                 if (o.Cin in (256, 512) and 256 <= o.Cout <= 2048) or \
                         (o.Cin in (1024, 2048) and o.Cout in (256, 512, 1024, 2048)):
                     want = "pw_pipe"          # pipelined-epilogue kernel for the instantiated widths
-                elif nt and o.Cout >= 64 * nt:
-                    want = "pw_stream"
                 elif o.Cin % 128 == 0 and o.Cin <= 1024:
                     want = "pw_tile"
-                elif o.Cin % 256 == 0:
-                    want = "pw_mfma"
                 else:
                     want = "gemm_mfma"
             else:
@@ -299,18 +337,12 @@ def test_benchmark_shapes_use_the_matrix_core_kernels():
 
 
 # ----------------------------------------------------------------------------- encoders
-def check_encoder(net, seed, items=None, **draw_kw):
-    """GPU forward of the whole batch vs the oracle on the chosen batch items (each item of the
-    batch is an independent utterance, so its output equals the oracle run on that item alone)."""
-    params = W.draw_net_params(net, seed, **draw_kw)
-    x = W.draw_input(net, seed)
-    g = GpuNet(net, params)
-    y = g.forward(dev(x)).cpu().numpy()
-    torch.cuda.synchronize()
-    items = list(range(net.B)) if items is None else items
+def oracle_items(net, params, x, y, items, what):
+    """Oracle on the given batch items (each item of the batch is an independent utterance, so its
+    output equals the oracle run on that item alone), compared with rows of the GPU output y."""
+    sub = W.NetSpec(net.name, net.config_id, 1, net.Cin, net.Tin, net.ops, net.n_slots)
     for b in items:
-        say(f"  oracle on {net.name} seed={seed} item {b}")
-        sub = W.NetSpec(net.name, net.config_id, 1, net.Cin, net.Tin, net.ops, net.n_slots)
+        say(f"  oracle on {what} item {b}")
         ref, outs = oracle.encoder_forward(sub, params, np.ascontiguousarray(x[b:b + 1]), keep=True)
         if not np.array_equal(y[b:b + 1], ref):
             # localise: replay op by op on the GPU from the oracle's intermediates
@@ -320,13 +352,43 @@ def check_encoder(net, seed, items=None, **draw_kw):
                 if getattr(op, "more_res", None):
                     r = [r] + [slots[q] for q in op.more_res]
                 got = gpu_layer(op, 1, p, slots[op.in_slot], r, packed=(not op.depthwise and op.k > 1))
-                assert np.array_equal(got, outs[i]), f"first failing op {i} {op.name} ({g.kernels()[i]})"
+                assert np.array_equal(got, outs[i]), f"item {b}: first failing op {i} {op.name}"
                 slots[op.out_slot] = outs[i]
-            raise AssertionError("encoder output differs although every op matches in isolation")
+            raise AssertionError(f"item {b}: encoder output differs although every op matches in isolation")
         flat = ref.reshape(-1)
         assert len(set(flat.tolist())) > 16, "degenerate reference output"
-    g.enc.close()
+
+
+_gpu_runs = {}
+
+
+def gpu_forward_cached(key, make_net, seed, **draw_kw):
+    """(net, params, x, y) of one GPU forward of the whole batch, computed once per key and shared by
+    the tests that compare groups of its batch items with the oracle."""
+    if key not in _gpu_runs:
+        _gpu_runs.clear()                           # one full-size network at a time
+        net = make_net()
+        params = W.draw_net_params(net, seed, **draw_kw)
+        x = W.draw_input(net, seed)
+        g = GpuNet(net, params)
+        y = g.forward(dev(x)).cpu().numpy()
+        g.check_guards()
+        g.enc.close()
+        _gpu_runs[key] = (net, params, x, y)
+    return _gpu_runs[key]
+
+
+def check_encoder(net, seed, items=None, **draw_kw):
+    """GPU forward of the whole batch vs the oracle on the chosen batch items (default: all)."""
+    net_, params, x, y = gpu_forward_cached((net.name, net.config_id, net.B, net.Tin, len(net.ops), seed), lambda: net,
+                                            seed, **draw_kw)
+    oracle_items(net_, params, x, y, list(range(net.B)) if items is None else items, f"{net.name} seed={seed}")
     return y
+
+
+def truncated(net, n_ops):
+    """The first n_ops ops of a network as a network of its own (its output: that op's output)."""
+    return W.NetSpec(f"{net.name}[:{n_ops}]", net.config_id, net.B, net.Cin, net.Tin, net.ops[:n_ops], net.n_slots)
 
 
 @pytest.mark.parametrize("seed", range(1, 21))
@@ -343,6 +405,7 @@ def test_tiny_encoders(cfg):
     x = W.draw_input(net, 3)
     g = GpuNet(net, params)
     y = g.forward(dev(x)).cpu().numpy()
+    g.check_guards()
     assert np.array_equal(y, oracle.encoder_forward(net, params, x))
 
 
@@ -352,27 +415,45 @@ def test_config1_quartznet_5x5(seed):
     check_encoder(W.build_config(1), seed)
 
 
+# Configurations 2 to 4 at full size, in the launch configuration the benchmark times: the oracle
+# checks EVERY batch item (the kernels' tiles straddle the items at a different offset for each).
+# The items are spread over several tests so that none of them is silent for long.
+@pytest.mark.parametrize("half", [0, 1])
 @pytest.mark.parametrize("seed", [1, 2, 3])
-def test_config2_quartznet_15x5_batch32(seed):
-    """Full size, the launch configuration the benchmark times; oracle on sampled items."""
-    say(f"config2 seed={seed}")
-    check_encoder(W.build_config(2), seed, items=[0, 31] if seed == 1 else [seed * 7])
+def test_config2_quartznet_15x5_batch32(seed, half):
+    say(f"config2 seed={seed} items {16 * half}..{16 * half + 15}")
+    check_encoder(W.build_config(2), seed, items=range(16 * half, 16 * half + 16))
 
 
-@pytest.mark.parametrize("seed", [1, 2, 3])
+@pytest.mark.parametrize("n_ops,items", [(12, range(32)), (23, [0, 9, 18, 31]), (167, [0, 13, 31])],
+                         ids=["block1_end", "block2_end", "C2_depthwise"])
+def test_config2_intermediate_tensors(n_ops, items):
+    """Outputs inside the network (the end of the first and second block, the output of the dilated
+    depthwise layer before the last pointwise layers), so that the saturating layers downstream
+    cannot hide a wrong byte: the first n_ops ops run as an encoder of their own."""
+    net = truncated(W.build_config(2), n_ops)
+    say(f"config2 truncated after op {n_ops - 1} ({net.ops[-1].name})")
+    check_encoder(net, 1, items=items)
+
+
+@pytest.mark.parametrize("group", [0, 1, 2, 3])
+def test_config3_jasper_10x5_batch16_seed1_every_item(group):
+    say(f"config3 seed=1 items {4 * group}..{4 * group + 3}")
+    check_encoder(W.build_config(3), 1, items=range(4 * group, 4 * group + 4))
+
+
+@pytest.mark.parametrize("seed", [2, 3])
 def test_config3_jasper_10x5_batch16(seed):
+    """Further seeds: two full-size items each, and the whole of a B=2, T=400 instance."""
     say(f"config3 seed={seed}")
-    if seed == 1:
-        check_encoder(W.build_config(3), seed, items=[15])
-    else:
-        # other seeds at a quarter of the frames (same ops, B=2): keeps the oracle to seconds
-        check_encoder(W.jasper(2, 400, config_id=3), seed)
+    check_encoder(W.build_config(3), seed, items=[seed, 15 - seed])
+    check_encoder(W.jasper(2, 400, config_id=3), seed)
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_config4_conformer_shaped_batch16(seed):
     say(f"config4 seed={seed}")
-    check_encoder(W.build_config(4), seed, items=[seed])
+    check_encoder(W.build_config(4), seed)
 
 
 def test_forward_is_deterministic_and_leaves_guard_bytes():
