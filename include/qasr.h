@@ -279,6 +279,21 @@ size_t qasr_encoder_workspace_bytes(const qasr_encoder* e);
 qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y,
                                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* qasr_encoder_forward for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * activation slots live in a static device array inside the library, qasr_static_workspace_bytes()
+ * = 32 MiB per GPU, held from the moment the library is loaded on that GPU until the process ends.
+ * The call allocates nothing and frees nothing; x and y are still the caller's.  An encoder whose
+ * qasr_encoder_workspace_bytes exceeds the array gives QASR_ERR_WORKSPACE (before any HIP call).
+ * All calls on one GPU share that GPU's array, on every stream: two such forwards that overlap in
+ * time on one GPU race (order them on one stream, or use qasr_encoder_forward with workspaces of
+ * their own).  The array keeps what the last call left; no slot is read before this forward has
+ * written it, so nothing needs clearing.  The device address of the array is looked up at the first
+ * call on each GPU (that first call should not happen under stream capture).  Otherwise as
+ * qasr_encoder_forward: same kernels, same bits. */
+size_t qasr_static_workspace_bytes(void);
+qasr_status qasr_encoder_forward_static(const qasr_encoder* e, const int8_t* x, int8_t* y, void* stream);
+
 /* The forward from float features to float outputs: Eq. 1's quantiser on x (float32
  * [B,Cin,Tin], clipping range alpha, see qasr_quantize), the integer encoder, the dequantiser
  * S_out * q on its output (float32 [B,Cout,Tout], see qasr_dequantize).  The int8 copies of input

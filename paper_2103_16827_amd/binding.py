@@ -89,6 +89,10 @@ def lib():
         L.qasr_encoder_workspace_bytes.argtypes = [_vp]
         L.qasr_encoder_forward.restype = _i32
         L.qasr_encoder_forward.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.qasr_encoder_forward_static.restype = _i32
+        L.qasr_encoder_forward_static.argtypes = [_vp, _vp, _vp, _vp]
+        L.qasr_static_workspace_bytes.restype = ctypes.c_size_t
+        L.qasr_static_workspace_bytes.argtypes = []
         L.qasr_encoder_forward_timed.restype = _i32
         L.qasr_encoder_forward_timed.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float)]
         L.qasr_encoder_graph_create.restype = _i32
@@ -158,6 +162,10 @@ def make_desc(B, Cin, Cout, Tin, k=1, stride=1, dilation=1, pad_left=0, pad_righ
               x_batch_stride=0, y_batch_stride=0, flags=0) -> ConvDesc:
     return ConvDesc(B, Cin, Cout, Tin, k, stride, dilation, pad_left, pad_right, groups,
                     x_batch_stride, y_batch_stride, flags)
+
+
+def static_workspace_bytes() -> int:
+    return int(lib().qasr_static_workspace_bytes())
 
 
 def tuning_reload() -> None:
@@ -299,6 +307,11 @@ class Encoder:
         _check(lib().qasr_encoder_forward(self._h, _ptr(x), _ptr(y), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream()),
                "qasr_encoder_forward")
+        return y
+
+    def forward_static(self, x, y):
+        """qasr_encoder_forward_static: the slots live in the library's static device array."""
+        _check(lib().qasr_encoder_forward_static(self._h, _ptr(x), _ptr(y), _stream()), "qasr_encoder_forward_static")
         return y
 
     @property

@@ -5,6 +5,7 @@
 #include "tuning.hpp"
 
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -524,6 +525,51 @@ static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* 
 qasr_status qasr_encoder_forward(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
                                  size_t workspace_bytes, void* stream) {
   return forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+}
+
+// ---- the forward for callers that can neither allocate nor pass a workspace: the activation slots
+// live in a static device array of the library.  The array's name is only a host-side stand-in; its
+// device address is looked up once per device and kept.
+#define QASR_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+static __device__ __align__(256) unsigned char scratch[QASR_STATIC_WORKSPACE_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// device address of `scratch` on the current device (looked up at the first call on that device)
+qasr_status static_scratch(void** out) {
+  int dev = 0;
+  const hipError_t ge = hipGetDevice(&dev);
+  if (ge != hipSuccess) return hip_status(ge);
+  if (dev < 0 || dev >= kMaxDevices) return QASR_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t se = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (se != hipSuccess) return hip_status(se);
+    if (!ptr || ((uintptr_t)ptr & 255)) return QASR_ERR_WORKSPACE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return QASR_OK;
+}
+
+}  // namespace
+
+size_t qasr_static_workspace_bytes(void) { return QASR_STATIC_WORKSPACE_BYTES; }
+
+qasr_status qasr_encoder_forward_static(const qasr_encoder* e, const int8_t* x, int8_t* y, void* stream) {
+  if (!e || !x || !y) return QASR_ERR_NULL;
+  if (e->ws_bytes > QASR_STATIC_WORKSPACE_BYTES) return QASR_ERR_WORKSPACE;     // before any HIP call
+  void* ws = nullptr;
+  const qasr_status st = static_scratch(&ws);
+  if (st != QASR_OK) return st;
+  // every slot is written in full by the op that produces it before any op reads it: nothing in the
+  // array has to start at zero, whatever an earlier call left there
+  return forward_impl(e, x, y, ws, QASR_STATIC_WORKSPACE_BYTES, (hipStream_t)stream, nullptr);
 }
 
 size_t qasr_encoder_workspace_bytes_f32(const qasr_encoder* e) {
