@@ -340,6 +340,32 @@ const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i);
  * the op has none; -1 if i is out of range.  Same bits either way. */
 int32_t qasr_encoder_op_act_fused(const qasr_encoder* e, int32_t i);
 
+/* Runs of layers in one launch.  Where at least 8 utterances (one per XCD) go through a stretch of
+ * consecutive pointwise layers of 256 or 512 input channels and stride-1 depthwise layers (the blocks
+ * of the QuartzNet family), qasr_encoder_create plans that stretch as ONE launch of a persistent
+ * kernel: every XCD takes its share of the utterances through all of the stretch's layers, with
+ * barriers among that XCD's workgroups only, the activations staying in its L2 (every result bit is
+ * the same: the layers are the same integer arithmetic).  qasr_encoder_forward, _forward_static,
+ * _forward_f32 and the graph entry points use the plan; x and y must then be 16-byte aligned
+ * (otherwise, and with QASR_NO_TEAM set in the environment, every layer is launched by itself).
+ *   qasr_encoder_op_in_team: 1 if op i is inside such a run, 0 if not, -1 if i is out of range.
+ *   qasr_encoder_forward_layerwise: the forward with every layer as a launch of its own, whatever
+ *     the plan (same arguments and errors as qasr_encoder_forward).
+ *   qasr_encoder_team_check: after the caller has synchronised the stream: *aborted = 1 if a wait
+ *     inside a persistent kernel of the last forward gave up (its waits are bounded: about a second;
+ *     the outputs of that forward are then invalid), else 0.  Synchronous (a small copy).
+ *   qasr_encoder_forward_team_stamps: the forward with the persistent kernels' clock stamps on;
+ *     synchronises and writes to op_us[0..n_ops) (HOST) the time in microseconds between the ends of
+ *     consecutive layers inside a run, as seen by the first workgroup of the first XCD (0 for ops
+ *     outside runs).  For profiling only. */
+int32_t qasr_encoder_op_in_team(const qasr_encoder* e, int32_t i);
+qasr_status qasr_encoder_forward_layerwise(const qasr_encoder* e, const int8_t* x, int8_t* y,
+                                           void* workspace, size_t workspace_bytes, void* stream);
+qasr_status qasr_encoder_team_check(const qasr_encoder* e, int32_t* aborted);
+qasr_status qasr_encoder_forward_team_stamps(const qasr_encoder* e, const int8_t* x, int8_t* y,
+                                             void* workspace, size_t workspace_bytes, void* stream,
+                                             float* op_us);
+
 void qasr_encoder_destroy(qasr_encoder* e);
 
 /* Name of the kernel family qasr_conv1d_int8 would dispatch this descriptor to (host-only). */

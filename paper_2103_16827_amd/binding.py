@@ -93,6 +93,14 @@ def lib():
         L.qasr_encoder_forward_static.argtypes = [_vp, _vp, _vp, _vp]
         L.qasr_static_workspace_bytes.restype = ctypes.c_size_t
         L.qasr_static_workspace_bytes.argtypes = []
+        L.qasr_encoder_forward_layerwise.restype = _i32
+        L.qasr_encoder_forward_layerwise.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+        L.qasr_encoder_op_in_team.restype = _i32
+        L.qasr_encoder_op_in_team.argtypes = [_vp, _i32]
+        L.qasr_encoder_team_check.restype = _i32
+        L.qasr_encoder_team_check.argtypes = [_vp, ctypes.POINTER(_i32)]
+        L.qasr_encoder_forward_team_stamps.restype = _i32
+        L.qasr_encoder_forward_team_stamps.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float)]
         L.qasr_encoder_forward_timed.restype = _i32
         L.qasr_encoder_forward_timed.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_float)]
         L.qasr_encoder_graph_create.restype = _i32
@@ -308,6 +316,30 @@ class Encoder:
                                           workspace.numel() * workspace.element_size(), _stream()),
                "qasr_encoder_forward")
         return y
+
+    def forward_layerwise(self, x, y, workspace):
+        """qasr_encoder_forward_layerwise: every layer as a launch of its own."""
+        _check(lib().qasr_encoder_forward_layerwise(self._h, _ptr(x), _ptr(y), _ptr(workspace),
+                                                    workspace.numel() * workspace.element_size(), _stream()),
+               "qasr_encoder_forward_layerwise")
+        return y
+
+    def op_in_team(self, i: int) -> bool:
+        return lib().qasr_encoder_op_in_team(self._h, i) == 1
+
+    def team_aborted(self) -> bool:
+        """qasr_encoder_team_check (synchronise first): a bounded wait of a persistent kernel gave up."""
+        a = _i32(0)
+        _check(lib().qasr_encoder_team_check(self._h, ctypes.byref(a)), "qasr_encoder_team_check")
+        return bool(a.value)
+
+    def forward_team_stamps(self, x, y, workspace):
+        """qasr_encoder_forward_team_stamps: per-op microseconds inside the persistent kernels (0 elsewhere)."""
+        us = (ctypes.c_float * self.n_ops)()
+        _check(lib().qasr_encoder_forward_team_stamps(self._h, _ptr(x), _ptr(y), _ptr(workspace),
+                                                      workspace.numel() * workspace.element_size(), _stream(), us),
+               "qasr_encoder_forward_team_stamps")
+        return list(us)
 
     def forward_static(self, x, y):
         """qasr_encoder_forward_static: the slots live in the library's static device array."""

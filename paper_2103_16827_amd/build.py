@@ -119,6 +119,10 @@ def build(verbose: bool = False) -> str:
             if os.path.exists(LIB):
                 os.remove(LIB)
             raise RuntimeError(f"{asm}: register read right after a partial write: {bad[0][0]} | {bad[0][1]}")
+    if not recs:       # no figures parsed (the remark's format changed?): nothing was checked
+        if os.path.exists(LIB):
+            os.remove(LIB)
+        raise RuntimeError("the compiler reported no per-kernel resource usage: the scratch-memory check cannot run")
     spilled = kernels_using_scratch(recs)
     if spilled:
         if os.path.exists(LIB):

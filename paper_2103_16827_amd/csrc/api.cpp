@@ -2,6 +2,7 @@
 // encoder executor (a flat op list over activation slots).  See include/qasr.h.
 #include "../../include/qasr.h"
 #include "kernels.hpp"
+#include "team.hpp"
 #include "tuning.hpp"
 
 #include <cmath>
@@ -139,7 +140,123 @@ struct qasr_encoder {
   size_t ws_bytes = 0;
   size_t in_elems = 0, out_elems = 0;   // int8 elements of the network input and output
   int8_t* packed = nullptr;       // device: packed weights of all groups == 1 layers
+  // Runs of consecutive ops that one launch of the persistent team kernel executes (team.hip); the
+  // ops outside them are launched one by one.
+  struct TeamRun {
+    int32_t first = 0, count = 0;
+    qasr::TeamOp* ops_dev = nullptr;
+    qasr::TeamCtl* ctl = nullptr;
+  };
+  std::vector<TeamRun> runs;
+  std::vector<int32_t> run_of;    // per op: index into runs, or -1
+  int8_t* toeplitz = nullptr;     // device: Toeplitz operand images of the depthwise layers inside runs
+  int32_t team_wgs = 0;           // workgroups of a team launch (one per compute unit)
 };
+
+
+// ---- team runs: which ops one launch of the persistent kernel takes (host logic only until the
+// device arrays are filled).  A run is a maximal stretch of consecutive ops whose shapes the team
+// kernel's layer bodies take; it needs at least 8 utterances (one per XCD) and 3 ops to pay.
+constexpr int32_t kMinRunOps = 3;
+
+static bool team_record(const qasr_encoder::Op& op, qasr::TeamOp& t) {
+  if (op.has_act || op.n_more_res > 0) return false;
+  t = qasr::TeamOp{};
+  const ConvParams& p = op.p;
+  if (p.depthwise) {
+    if (!qasr::team_dw_geometry(p, t)) return false;
+    t.kind = 1;
+  } else {
+    if (!qasr::team_pw_geometry(p, t)) return false;
+    t.kind = 0;
+  }
+  t.xbs = p.xbs; t.ybs = p.ybs;
+  t.Cin = p.Cin; t.Cout = p.Cout; t.T = p.Tin;
+  t.relu = p.relu;
+  t.w = p.w; t.bias = p.bias; t.m = p.m; t.s = p.s;
+  return true;
+}
+
+static qasr_status plan_team_runs(qasr_encoder* e, int32_t n_slots) {
+  const int32_t n = (int32_t)e->ops.size();
+  e->run_of.assign(n, -1);
+  if (qasr::tuning().no_team || n < kMinRunOps || e->ops[0].d.B < 8 || n > qasr::kTeamMaxStamps - 2) return QASR_OK;
+  std::vector<qasr::TeamOp> rec(n);
+  std::vector<char> can(n, 0);
+  bool any = false;
+  for (int32_t i = 0; i < n; ++i) {
+    can[i] = team_record(e->ops[i], rec[i]) ? 1 : 0;
+    any = any || can[i];
+  }
+  if (!any) return QASR_OK;
+  e->team_wgs = qasr::team_workgroups();        // (first HIP call of the planner)
+  if (e->team_wgs <= 0) return QASR_OK;
+
+  // runs, Toeplitz images
+  size_t toep_bytes = 0;
+  for (int32_t i = 0; i < n;) {
+    if (!can[i]) { ++i; continue; }
+    int32_t j = i;
+    while (j < n && can[j]) ++j;
+    if (j - i >= kMinRunOps) {
+      qasr_encoder::TeamRun r;
+      r.first = i;
+      r.count = j - i;
+      for (int32_t q = i; q < j; ++q) {
+        e->run_of[q] = (int32_t)e->runs.size();
+        if (rec[q].kind == 1) toep_bytes += round256(qasr::team_toeplitz_bytes(rec[q], rec[q].Cout));
+      }
+      e->runs.push_back(r);
+    }
+    i = j;
+  }
+  if (e->runs.empty()) return QASR_OK;
+  if (toep_bytes) {
+    const hipError_t me = hipMalloc((void**)&e->toeplitz, toep_bytes);
+    if (me != hipSuccess) return hip_status(me);
+  }
+  size_t toff = 0;
+  for (qasr_encoder::TeamRun& r : e->runs) {
+    // a barrier goes before an op that touches what an op since the last barrier wrote, or writes
+    // what one of them read (the first op of a run follows a kernel boundary)
+    std::vector<char> written(n_slots, 0), read(n_slots, 0);
+    for (int32_t q = r.first; q < r.first + r.count; ++q) {
+      const qasr_encoder::Op& op = e->ops[q];
+      qasr::TeamOp& t = rec[q];
+      const bool hazard = written[op.in_slot] || (op.res_slot >= 0 && written[op.res_slot]) ||
+                          written[op.out_slot] || read[op.out_slot];
+      t.sync_before = hazard ? 1 : 0;
+      if (hazard) {
+        std::fill(written.begin(), written.end(), 0);
+        std::fill(read.begin(), read.end(), 0);
+      }
+      read[op.in_slot] = 1;
+      if (op.res_slot >= 0) read[op.res_slot] = 1;
+      written[op.out_slot] = 1;
+      // operands: slot 0 is the network input, the last op's output the network output
+      t.in_kind = op.in_slot == 0 ? 0 : 1;
+      t.in_off = op.in_slot == 0 ? 0 : (int64_t)e->slot_off[op.in_slot];
+      t.res_kind = op.res_slot < 0 ? -1 : (op.res_slot == 0 ? 0 : 1);
+      t.res_off = op.res_slot <= 0 ? 0 : (int64_t)e->slot_off[op.res_slot];
+      t.out_kind = (q + 1 == n) ? 2 : 1;
+      t.out_off = (q + 1 == n) ? 0 : (int64_t)e->slot_off[op.out_slot];
+      if (t.kind == 1) {
+        int8_t* img = e->toeplitz + toff;
+        toff += round256(qasr::team_toeplitz_bytes(t, t.Cout));
+        const hipError_t te = qasr::launch_toeplitz_image(op.p.w, op.p.Cout, op.p.k, op.p.dil, t, img, nullptr);
+        if (te != hipSuccess) return hip_status(te);
+        t.w = img;
+      }
+    }
+    hipError_t me = hipMalloc((void**)&r.ops_dev, sizeof(qasr::TeamOp) * (size_t)r.count);
+    if (me == hipSuccess) me = hipMalloc((void**)&r.ctl, sizeof(qasr::TeamCtl));
+    if (me == hipSuccess)
+      me = hipMemcpy(r.ops_dev, rec.data() + r.first, sizeof(qasr::TeamOp) * (size_t)r.count, hipMemcpyHostToDevice);
+    if (me == hipSuccess) me = hipMemset(r.ctl, 0, sizeof(qasr::TeamCtl));
+    if (me != hipSuccess) return hip_status(me);
+  }
+  return QASR_OK;
+}
 
 extern "C" {
 
@@ -465,7 +582,14 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
       }
     }
   }
-  if (packed_bytes) {
+  {
+    const qasr_status ts = plan_team_runs(e, n_slots);
+    if (ts != QASR_OK) {
+      qasr_encoder_destroy(e);
+      return ts;
+    }
+  }
+  if (packed_bytes || !e->runs.empty()) {
     const hipError_t se = hipStreamSynchronize(nullptr);
     if (se != hipSuccess) {
       qasr_encoder_destroy(e);
@@ -490,14 +614,31 @@ int32_t qasr_encoder_op_act_fused(const qasr_encoder* e, int32_t i) {
   return e->ops[i].act_fused ? 1 : 0;
 }
 
+// team: 0 = every op as a launch of its own, 1 = the planned runs through the team kernel,
+// 2 = the same with the team kernel's per-layer clock stamps switched on
+int32_t qasr_encoder_op_in_team(const qasr_encoder* e, int32_t i) {
+  if (!e || i < 0 || i >= (int32_t)e->ops.size()) return -1;
+  return e->run_of.empty() ? 0 : (e->run_of[i] >= 0 ? 1 : 0);
+}
+
 static qasr_status forward_impl(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
-                                size_t workspace_bytes, hipStream_t st, hipEvent_t* ev) {
+                                size_t workspace_bytes, hipStream_t st, hipEvent_t* ev, int team = 1) {
   if (!e || !x || !y) return QASR_ERR_NULL;
   if (e->ws_bytes && (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < e->ws_bytes))
     return QASR_ERR_WORKSPACE;
   int8_t* ws = (int8_t*)workspace;
   const size_t n = e->ops.size();
+  // (the team kernel's loads want 16-byte aligned tensors, like the kernels it replaces)
+  const bool use_team = team && !ev && !e->runs.empty() && ((uintptr_t)x % 16 == 0) && ((uintptr_t)y % 16 == 0);
   for (size_t i = 0; i < n; ++i) {
+    if (use_team && e->run_of[i] >= 0) {
+      const qasr_encoder::TeamRun& r = e->runs[e->run_of[i]];
+      const hipError_t te = qasr::launch_team(r.ops_dev, r.count, x, ws, y, e->ops[0].d.B, r.ctl, e->team_wgs,
+                                              team == 2 ? 1 : 0, st);
+      if (te != hipSuccess) return hip_status(te);
+      i = (size_t)(r.first + r.count) - 1;
+      continue;
+    }
     const qasr_encoder::Op& op = e->ops[i];
     ConvParams p = op.p;
     p.x = op.in_slot == 0 ? x : ws + e->slot_off[op.in_slot];
@@ -572,6 +713,42 @@ qasr_status qasr_encoder_forward_static(const qasr_encoder* e, const int8_t* x, 
   return forward_impl(e, x, y, ws, QASR_STATIC_WORKSPACE_BYTES, (hipStream_t)stream, nullptr);
 }
 
+qasr_status qasr_encoder_forward_layerwise(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  return forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr, 0);
+}
+
+qasr_status qasr_encoder_team_check(const qasr_encoder* e, int32_t* aborted) {
+  if (!e || !aborted) return QASR_ERR_NULL;
+  *aborted = 0;
+  for (const qasr_encoder::TeamRun& r : e->runs) {
+    uint32_t flag = 0;
+    const hipError_t ce = hipMemcpy(&flag, &r.ctl->abort, sizeof(flag), hipMemcpyDeviceToHost);
+    if (ce != hipSuccess) return hip_status(ce);
+    if (flag) *aborted = 1;
+  }
+  return QASR_OK;
+}
+
+qasr_status qasr_encoder_forward_team_stamps(const qasr_encoder* e, const int8_t* x, int8_t* y, void* workspace,
+                                             size_t workspace_bytes, void* stream, float* op_us) {
+  if (!e || !op_us) return QASR_ERR_NULL;
+  const size_t n = e->ops.size();
+  for (size_t i = 0; i < n; ++i) op_us[i] = 0.f;
+  qasr_status st = forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr, 2);
+  if (st != QASR_OK) return st;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return QASR_ERR_HIP;
+  std::vector<unsigned long long> stamp(qasr::kTeamMaxStamps);
+  for (const qasr_encoder::TeamRun& r : e->runs) {
+    const hipError_t ce = hipMemcpy(stamp.data(), r.ctl->stamp, sizeof(unsigned long long) * (size_t)(r.count + 1),
+                                    hipMemcpyDeviceToHost);
+    if (ce != hipSuccess) return hip_status(ce);
+    for (int32_t q = 0; q < r.count; ++q)       // the clock runs at 100 MHz
+      op_us[r.first + q] = (float)((double)(stamp[q + 1] - stamp[q]) * 0.01);
+  }
+  return st;
+}
+
 size_t qasr_encoder_workspace_bytes_f32(const qasr_encoder* e) {
   return e ? e->ws_bytes + round256(e->in_elems) + round256(e->out_elems) : 0;
 }
@@ -605,7 +782,7 @@ qasr_status qasr_encoder_forward_timed(const qasr_encoder* e, const int8_t* x, i
   // totals, spread evenly, is taken off every op's interval, so that the op times add up to the
   // duration of the undisturbed forward.
   if (st == QASR_OK && hipEventRecord(cal[0], (hipStream_t)stream) != hipSuccess) st = QASR_ERR_HIP;
-  if (st == QASR_OK) st = forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr);
+  if (st == QASR_OK) st = forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, nullptr, 0);
   if (st == QASR_OK && hipEventRecord(cal[1], (hipStream_t)stream) != hipSuccess) st = QASR_ERR_HIP;
   if (st == QASR_OK) st = forward_impl(e, x, y, workspace, workspace_bytes, (hipStream_t)stream, ev.data());
   if (st == QASR_OK && hipEventSynchronize(ev[n]) != hipSuccess) st = QASR_ERR_HIP;
@@ -678,6 +855,11 @@ void qasr_encoder_graph_destroy(qasr_encoder_graph* g) {
 void qasr_encoder_destroy(qasr_encoder* e) {
   if (!e) return;
   if (e->packed) (void)hipFree(e->packed);
+  if (e->toeplitz) (void)hipFree(e->toeplitz);
+  for (qasr_encoder::TeamRun& r : e->runs) {
+    if (r.ops_dev) (void)hipFree(r.ops_dev);
+    if (r.ctl) (void)hipFree(r.ctl);
+  }
   delete e;
 }
 

@@ -86,16 +86,17 @@ inline hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block,
   return hipLaunchKernel((const void*)kernel, grid, block, argv, shmem, st);
 }
 
-// Raises a kernel's dynamic-LDS limit to the chip's 160 KiB once per device: `done` (one per kernel
+// Raises a kernel's dynamic-LDS limit (to the chip's 160 KiB unless the kernel also has static LDS
+// and says how much dynamic LDS it needs) once per device: `done` (one per kernel
 // instantiation) holds a bit per device ordinal; two threads racing here both set the attribute,
 // which is harmless.  Devices beyond the mask's width set it on every launch.
-inline hipError_t ensure_max_dynamic_lds(const void* kernel, std::atomic<uint64_t>& done) {
+inline hipError_t ensure_max_dynamic_lds(const void* kernel, std::atomic<uint64_t>& done, int bytes = 160 * 1024) {
   int dev = 0;
   const hipError_t ge = hipGetDevice(&dev);
   if (ge != hipSuccess) return ge;
   const uint64_t bit = (dev >= 0 && dev < 64) ? (uint64_t)1 << dev : 0;
   if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
-  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
   return e;
 }

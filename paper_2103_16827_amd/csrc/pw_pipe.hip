@@ -40,7 +40,7 @@ using namespace pwp;
 template <int MT, int KCH, bool ACT>
 __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   extern __shared__ __align__(128) unsigned char xs[];
-  pw_pipe_tile<MT, KCH, ACT, false>(p, g, blockIdx.x, xs);
+  pw_pipe_tile<MT, KCH, ACT, false>(p, g, blockIdx.x, xs, (int)threadIdx.x);
 }
 
 struct Choice { int MT, KCH, splits; };

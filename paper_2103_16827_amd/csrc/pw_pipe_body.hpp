@@ -18,7 +18,7 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 constexpr int kStoreThrough = 17;
 constexpr int NT = 2;           // 16-channel columns per wave and pass
 constexpr int ROWS = 16 * NT;   // output channels of a wave and pass
-constexpr int LOOK = 4;         // weight chunks requested ahead of the one being multiplied
+constexpr int kLookW = 4;       // weight chunks requested ahead of the one being multiplied (the stand-alone kernel)
 constexpr int LOOKX = 3;        // activation chunks requested ahead in pass 0
 constexpr int kMaxMT = 7;       // groups per tile: two accumulator sets of 8 groups would not fit the registers
 constexpr int MAXP = 8;         // passes (Cout <= 2048): bounds the constants parked in LDS
@@ -52,14 +52,20 @@ constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS *
 // interleave, no pass split), activations and residual rows were written earlier in the same kernel
 // by other workgroups of this XCD, so they are loaded at device scope (past the vector cache, out of
 // the XCD's L2), and the output rows are stored write-back (the next layer reads them from that L2).
-template <int MT, int KCH, bool ACT, bool TEAM>
+// LOOK: weight chunks requested ahead of the one being multiplied (a ring of LOOK x NT x 4 registers).
+template <int MT, int KCH, bool ACT, bool TEAM, int LOOK = kLookW>
 __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom& g, unsigned vblock,
-                                             unsigned char* const xs) {
+                                             unsigned char* const xs, int tid) {
   constexpr int NB = MT * NT;                     // epilogue blocks of a pass
   static_assert(KCH == 4 || KCH == 8 || KCH == 16 || KCH == 32, "instantiated input widths");
   static_assert(KCH % LOOK == 0, "ring slot of a chunk");
 
-  const int tid = threadIdx.x, lane = tid & 63;
+  // `tid`: the thread's index in the workgroup (threadIdx.x).
+  // (inside the team kernel's layer loop: keeps everything derived from the thread id inside the
+  // tile, or the compiler computes the lane constants of every layer body once, ahead of the loop,
+  // and has to carry them through all the bodies in registers that do not exist)
+  if (TEAM) asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, gi = lane >> 4;
   // Workgroup -> tile: consecutive workgroups go round-robin to the 8 XCDs (one L2 each);
