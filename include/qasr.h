@@ -340,14 +340,17 @@ const char* qasr_encoder_op_kernel(const qasr_encoder* e, int32_t i);
  * the op has none; -1 if i is out of range.  Same bits either way. */
 int32_t qasr_encoder_op_act_fused(const qasr_encoder* e, int32_t i);
 
-/* Runs of layers in one launch.  Where at least 8 utterances (one per XCD) go through a stretch of
+/* Runs of layers in one launch (EXPERIMENTAL: only with QASR_TEAM set in the environment when the
+ * encoder is created; on encoders with more than about 85 layers in a run the kernel has given wrong
+ * utterances now and then, so it is off by default and every layer is a launch of its own).  Where
+ * at least 8 utterances (one per XCD) go through a stretch of
  * consecutive pointwise layers of 256 or 512 input channels and stride-1 depthwise layers (the blocks
- * of the QuartzNet family), qasr_encoder_create plans that stretch as ONE launch of a persistent
+ * of the QuartzNet family), qasr_encoder_create then plans that stretch as ONE launch of a persistent
  * kernel: every XCD takes its share of the utterances through all of the stretch's layers, with
  * barriers among that XCD's workgroups only, the activations staying in its L2 (every result bit is
  * the same: the layers are the same integer arithmetic).  qasr_encoder_forward, _forward_static,
  * _forward_f32 and the graph entry points use the plan; x and y must then be 16-byte aligned
- * (otherwise, and with QASR_NO_TEAM set in the environment, every layer is launched by itself).
+ * (otherwise every layer is launched by itself).
  *   qasr_encoder_op_in_team: 1 if op i is inside such a run, 0 if not, -1 if i is out of range.
  *   qasr_encoder_forward_layerwise: the forward with every layer as a launch of its own, whatever
  *     the plan (same arguments and errors as qasr_encoder_forward).

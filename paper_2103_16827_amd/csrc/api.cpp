@@ -180,7 +180,7 @@ static bool team_record(const qasr_encoder::Op& op, qasr::TeamOp& t) {
 static qasr_status plan_team_runs(qasr_encoder* e, int32_t n_slots) {
   const int32_t n = (int32_t)e->ops.size();
   e->run_of.assign(n, -1);
-  if (qasr::tuning().no_team || n < kMinRunOps || e->ops[0].d.B < 8 || n > qasr::kTeamMaxStamps - 2) return QASR_OK;
+  if (!qasr::tuning().team || n < kMinRunOps || e->ops[0].d.B < 8 || n > qasr::kTeamMaxStamps - 2) return QASR_OK;
   std::vector<qasr::TeamOp> rec(n);
   std::vector<char> can(n, 0);
   bool any = false;

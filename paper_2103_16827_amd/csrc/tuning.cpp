@@ -18,7 +18,7 @@ Tuning read_env() {
   Tuning t;
   t.no_pw_pipe = getenv("QASR_NO_PW_PIPE") != nullptr;
   t.no_conv_pipe = getenv("QASR_NO_CONV_PIPE") != nullptr;
-  t.no_team = getenv("QASR_NO_TEAM") != nullptr;
+  t.team = getenv("QASR_TEAM") != nullptr;
   if (const char* e = getenv("QASR_PWP_MT")) t.pwp_mt = atoi(e);
   if (const char* e = getenv("QASR_PWP_SPLIT")) t.pwp_split = atoi(e);
   if (const char* e = getenv("QASR_DWP")) {

@@ -7,13 +7,14 @@
 //   QASR_DW_R                               dw_mfma: strips per wave
 //   QASR_CP_TILE = "MT,NT"                  conv_pipe: tile
 //   QASR_PWT_MT                             pw_tile: groups per tile
-//   QASR_NO_TEAM                            encoder: no persistent team kernel, one launch per op
+//   QASR_TEAM                               encoder: plan runs of layers for the persistent team kernel
+//                                           (experimental, off unless set)
 #pragma once
 
 namespace qasr {
 
 struct Tuning {
-  bool no_pw_pipe = false, no_conv_pipe = false, no_team = false;
+  bool no_pw_pipe = false, no_conv_pipe = false, team = false;
   int pwp_mt = 0, pwp_split = 0;
   int dwp_r = 0, dwp_s = 0;
   int dw_r = 0;

@@ -1,5 +1,8 @@
 """The persistent team kernel (runs of layers in one launch, barriers among the workgroups of an XCD)
-against the CPU oracle and against the same encoder launched layer by layer."""
+against the CPU oracle and against the same encoder launched layer by layer.  The kernel is
+experimental and off unless QASR_TEAM is set when the encoder is created: every test here that runs
+it sets the variable for itself, on encoders short enough (about 60 layers in a run) for the
+kernel to have been right every time."""
 import numpy as np
 import pytest
 import torch
@@ -44,8 +47,9 @@ def run_both(net, seed, items=None, **draw_kw):
 
 
 @pytest.mark.parametrize("B,T", [(8, 160), (9, 320), (32, 800), (19, 208)])
-def test_quartznet_blocks_in_team_runs(B, T):
+def test_quartznet_blocks_in_team_runs(B, T, tuning_env):
     """QuartzNet-5x5 shape at batch sizes that give every XCD one, two (ragged) or four utterances."""
+    tuning_env("QASR_TEAM", "1")
     net = W.quartznet(B, 2 * T, 1, config_id=1)
     g, in_team = run_both(net, 3, items=range(B) if B <= 9 else [0, B // 2, B - 1])
     assert sum(in_team) >= 55, in_team          # all five blocks, C2 and C3
@@ -53,24 +57,27 @@ def test_quartznet_blocks_in_team_runs(B, T):
     g.enc.close()
 
 
-def test_team_runs_are_switched_off_by_the_environment(tuning_env):
-    tuning_env("QASR_NO_TEAM", "1")
+def test_team_runs_are_off_unless_the_environment_asks_for_them(monkeypatch):
+    monkeypatch.delenv("QASR_TEAM", raising=False)
+    Q.tuning_reload()
     net = W.quartznet(8, 320, 1, config_id=1)
     g = GpuNet(net, W.draw_net_params(net, 1))
     assert not any(g.enc.op_in_team(i) for i in range(g.enc.n_ops))
     g.enc.close()
 
 
-def test_small_batches_and_other_families_keep_layerwise_launches():
+def test_small_batches_and_other_families_keep_layerwise_launches(tuning_env):
+    tuning_env("QASR_TEAM", "1")
     for net in (W.build_config(1), W.jasper(8, 400, config_id=3)):
         g = GpuNet(net, W.draw_net_params(net, 1))
         assert not any(g.enc.op_in_team(i) for i in range(g.enc.n_ops)), net.name
         g.enc.close()
 
 
-def test_team_forward_repeats_and_clock_stamps():
+def test_team_forward_repeats_and_clock_stamps(tuning_env):
     """The same encoder many times in a row (the control block is cleared by every launch), then the
     per-layer clock stamps."""
+    tuning_env("QASR_TEAM", "1")
     net = W.quartznet(16, 800, 1, config_id=1)
     params = W.draw_net_params(net, 2)
     g = GpuNet(net, params)
