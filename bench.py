@@ -11,12 +11,19 @@ in HBM: one launch of the forward captured as a HIP graph (qasr_encoder_graph_la
               HIP events around every op (a separate, untimed-for-`value` pass)
   stages      spec view: depthwise stages against HBM peak, pointwise stages against the
               int8 MFMA peak (algorithmic bytes / MACs over summed per-op device time)
+  step_ms     mean / median / min / max of the timed steps, each bracketed by HIP events
+  ceilings    what this chip sustained in this process: a streaming int8 copy and a register-resident
+              int8 matrix-core loop; every fraction is given against the datasheet and against these
+  stages_cold the per-stage figures again with nothing left in the caches by the previous pass
+              (the passes rotate through buffer sets of more than 512 MB in all)
   cpu_baseline the CPU oracle timed on a bounded sample (batch items one at a time, about ten
               seconds of them) on the host cores; every item is also compared with the GPU output
+  cpu_baseline_1thread  the same oracle held to one thread, on configs[0] and configs[1]
 """
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -54,6 +61,37 @@ def measured_traffic(kernel, config):
     return None
 
 
+def oracle_child(config, max_seconds):
+    """Run in a child process (see cpu_1thread): the oracle on one batch item of a configuration,
+    repeated until max_seconds have gone; prints frames/s and the thread count as JSON."""
+    import numpy as np
+    import oracle
+    import qasr_workloads as W
+    net = W.build_config(config, 1)
+    params = W.draw_net_params(net, 1)
+    x = W.draw_input(net, 1)
+    n, dt = 0, 0.0
+    while n < 1 or (dt < max_seconds and n < 200):
+        t0 = time.perf_counter()
+        oracle.encoder_forward(net, params, x)
+        dt += time.perf_counter() - t0
+        n += 1
+    print(json.dumps({"value": n * net.Tin / dt, "unit": "frames/s", "cores": oracle.num_threads(), "kind": "oracle",
+                      "sample": f"configs[{config}] one batch item, {n} forwards ({n * W.net_macs(net) / 1e9:.2f} GMAC) "
+                                f"in {dt:.2f} s"}))
+
+
+def cpu_1thread(config, max_seconds):
+    """The oracle as it stands, held to one thread by OMP_NUM_THREADS in a child process that never
+    touches the GPU."""
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    r = subprocess.run([sys.executable, os.path.abspath(__file__), "--oracle-child", str(config),
+                        "--oracle-child-seconds", str(max_seconds)], env=env, capture_output=True, text=True, timeout=300)
+    if r.returncode != 0:
+        return {"error": r.stderr.strip()[-300:]}
+    return json.loads(r.stdout.strip().splitlines()[-1])
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,11 +110,23 @@ def main():
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="after the steps, run one plain elementwise int8 kernel that reads and writes this many MiB "
                          "(the known-size dispatch that calibrates the HBM byte counters of a --pmc run)")
+    ap.add_argument("--cold-mib", type=int, default=600,
+                    help="total size of the buffer sets the cold per-stage passes rotate through (0: skip them)")
+    ap.add_argument("--oracle-child", type=int, default=-1, help=argparse.SUPPRESS)
+    ap.add_argument("--oracle-child-seconds", type=float, default=4.0, help=argparse.SUPPRESS)
     args = ap.parse_args()
+    if args.oracle_child >= 0:
+        oracle_child(args.oracle_child, args.oracle_child_seconds)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (batch sharding across GPUs needs no kernel work "
               "and is not part of it); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    # the child processes of the one-thread oracle figures start before this process touches the GPU
+    cpu_1t = None
+    if not args.no_cpu_baseline:
+        cpu_1t = {"configs[0]": cpu_1thread(0, 2.0), "configs[1]": cpu_1thread(1, 4.0)}
 
     import numpy as np
     import torch
@@ -123,6 +173,46 @@ def main():
         return (time.perf_counter() - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
     ms_per_step, ms_per_step_events = timed(step, args.warmup, args.steps)
+
+    # the same steps once more, each between two events of its own: spread of the step time
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    per = np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps)])
+    step_ms = {"mean": float(per.mean()), "median": float(np.median(per)), "min": float(per.min()),
+               "max": float(per.max()), "how": "one HIP event pair per step, a pass of its own after the timed one"}
+    del evs
+
+    # ---- ceilings measured here: streaming copy (read + write) and register-resident int8 MFMA loop
+    def best_ms(fn, reps):
+        out = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            out.append(a.elapsed_time(b))
+        return float(np.median(out)), float(min(out))
+    cp_bytes = 1 << 30
+    cp_a = torch.zeros(cp_bytes, dtype=torch.int8, device="cuda")
+    cp_b = torch.empty_like(cp_a)
+    Q.probe_copy(cp_a, cp_b)
+    copy_med, copy_min = best_ms(lambda: Q.probe_copy(cp_a, cp_b), 7)
+    del cp_a, cp_b
+    mf_out = torch.zeros(Q.probe_mfma_outputs(), dtype=torch.int32, device="cuda")
+    mf_iters = 20000
+    mf_ops = Q.probe_mfma_i8(mf_iters, mf_out)
+    mf_med, mf_min = best_ms(lambda: Q.probe_mfma_i8(mf_iters, mf_out), 5)
+    ceilings = {
+        "hbm_copy_GBs": 2 * cp_bytes / (copy_med * 1e-3) / 1e9, "hbm_copy_GBs_best": 2 * cp_bytes / (copy_min * 1e-3) / 1e9,
+        "hbm_copy_what": "qasr_probe_copy, 1 GiB read + 1 GiB written per launch, median (and best) of 7",
+        "int8_mfma_TOPs": mf_ops / (mf_med * 1e-3) / 1e12, "int8_mfma_TOPs_best": mf_ops / (mf_min * 1e-3) / 1e12,
+        "int8_mfma_what": "qasr_probe_mfma_i8, v_mfma_i32_16x16x64_i8 from registers, 8 waves per SIMD, median (and best) of 5",
+        "datasheet": {"hbm_GBs": HBM_PEAK_GBS, "int8_mfma_TOPs": INT8_PEAK_TOPS}}
+    del mf_out
+    torch.cuda.empty_cache()
     # the other launch mode, for comparison (not the reported value)
     other_ms = None if args.eager else timed(lambda: enc.forward(x, y, ws), 3, max(5, args.steps // 5))[0]
     # The launch floor of this op list: a graph of as many dependent one-element kernels as the
@@ -201,24 +291,56 @@ def main():
         achieved = 2.0 * d["macs"] / d["launches"] / (avg_ms * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                     "frac": achieved / INT8_PEAK_TOPS, "traffic": None}
+    roofline["frac_of_measured_ceiling"] = achieved / (ceilings["hbm_copy_GBs"] if roofline["bound"] == "hbm"
+                                                       else ceilings["int8_mfma_TOPs"])
     roofline["traffic"] = measured_traffic(dom, args.config)
     roofline["avg_launch_us"] = avg_ms * 1e3
     roofline["launches_per_step"] = d["launches"]
     roofline["share_of_device_time"] = d["ms"] / float(op_ms.sum())
 
-    def stage(sel):
+    def stage(sel, t_ms):
         idx = [i for i, o in enumerate(net.ops) if sel(o)]
         if not idx:
             return None
-        ms = float(op_ms[idx].sum())
+        ms = float(t_ms[idx].sum())
         byts = sum(op_algorithmic(net.ops[i], net.B)[0] for i in idx)
         macs = sum(op_algorithmic(net.ops[i], net.B)[1] for i in idx)
-        return {"ops": len(idx), "ms": ms, "GB/s": byts / (ms * 1e-3) / 1e9, "hbm_frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                "TOP/s": 2 * macs / (ms * 1e-3) / 1e12, "mfma_frac": 2 * macs / (ms * 1e-3) / 1e12 / INT8_PEAK_TOPS}
-    stages = {"depthwise": stage(lambda o: o.depthwise),
-              "pointwise": stage(lambda o: not o.depthwise and o.k == 1),
-              "dense": stage(lambda o: not o.depthwise and o.k > 1),
-              "device_ms_sum": float(op_ms.sum()), "ms_per_step_events": ms_per_step_events}
+        gbs, tops = byts / (ms * 1e-3) / 1e9, 2 * macs / (ms * 1e-3) / 1e12
+        return {"ops": len(idx), "ms": ms, "GB/s": gbs, "hbm_frac": gbs / HBM_PEAK_GBS,
+                "hbm_frac_of_measured_copy": gbs / ceilings["hbm_copy_GBs"],
+                "TOP/s": tops, "mfma_frac": tops / INT8_PEAK_TOPS,
+                "mfma_frac_of_measured_loop": tops / ceilings["int8_mfma_TOPs"]}
+
+    def stage_table(t_ms):
+        return {"depthwise": stage(lambda o: o.depthwise, t_ms),
+                "pointwise": stage(lambda o: not o.depthwise and o.k == 1, t_ms),
+                "dense": stage(lambda o: not o.depthwise and o.k > 1, t_ms),
+                "device_ms_sum": float(t_ms.sum())}
+    stages = stage_table(op_ms)
+    stages["ms_per_step_events"] = ms_per_step_events
+
+    # ---- the same per-op times with cold caches: the passes rotate through enough (x, workspace, y)
+    # sets that a set, and the weights, were pushed out of L2 and the memory-side cache by more than
+    # 512 MB of other traffic before they are touched again; within a pass a layer still finds the
+    # previous layer's output where the pipeline leaves it
+    stages_cold = None
+    if args.cold_mib > 0:
+        set_bytes = ws.numel() + x.numel() + y.numel()
+        n_sets = max(2, -(-(args.cold_mib << 20) // set_bytes))
+        sets = [(x.clone(), torch.empty_like(ws), torch.empty_like(y)) for _ in range(n_sets)]
+        for xs_, ws_, ys_ in sets:                       # one untimed pass over every set
+            enc.forward(xs_, ys_, ws_)
+        torch.cuda.synchronize()
+        acc_cold = np.zeros(enc.n_ops)
+        for xs_, ws_, ys_ in sets:
+            acc_cold += np.array(enc.forward_timed(xs_, ys_, ws_))
+        same = all(bool(torch.equal(ys_, y)) for _, _, ys_ in sets)
+        stages_cold = stage_table(acc_cold / n_sets)
+        stages_cold["buffer_sets"] = n_sets
+        stages_cold["bytes_rotated"] = n_sets * set_bytes
+        stages_cold["outputs_equal_to_the_timed_steps"] = same
+        del sets
+        torch.cuda.empty_cache()
 
     # ---- the oracle on the host cores, on one batch item of the same workload
     cpu = None
@@ -242,7 +364,7 @@ def main():
     total_macs = W.net_macs(net)
     out = {
         "metric": "INT8 encoder frames/sec", "value": value, "unit": "frames/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "step_ms": step_ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": f"{workload_label} {net.name} B={net.B} T_in={net.Tin} ({len(net.ops)} ops)",
@@ -254,7 +376,9 @@ def main():
             "what": "graph replay of that many dependent one-element kernels"},
         "int8_TOPS_useful": 2 * total_macs / (ms_per_step * 1e-3) / 1e12,
         "int8_TOPS_frac_of_peak": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / INT8_PEAK_TOPS,
-        "roofline": roofline, "stages": stages, "cpu_baseline": cpu,
+        "int8_TOPS_frac_of_measured_loop": 2 * total_macs / (ms_per_step * 1e-3) / 1e12 / ceilings["int8_mfma_TOPs"],
+        "roofline": roofline, "ceilings": ceilings, "stages": stages, "stages_cold": stages_cold,
+        "cpu_baseline": cpu, "cpu_baseline_1thread": cpu_1t,
     }
     print(json.dumps(out))
 

@@ -371,6 +371,19 @@ qasr_status qasr_encoder_forward_team_stamps(const qasr_encoder* e, const int8_t
 
 void qasr_encoder_destroy(qasr_encoder* e);
 
+/* Measured ceilings, for benchmarks that quote a kernel against what this chip sustains and not
+ * only against its datasheet (no passage of the paper: measurement support, not part of the path).
+ *   qasr_probe_copy: one streaming kernel that copies `bytes` (a multiple of 16; src, dst device,
+ *     16-byte aligned, not overlapping; else QASR_ERR_SHAPE / QASR_ERR_ALIAS) -- time it to get the
+ *     rate HBM sustains for a read plus a write.
+ *   qasr_probe_mfma_i8: one kernel whose waves issue v_mfma_i32_16x16x64_i8 from registers only
+ *     (8 independent accumulators per wave, `iters` rounds, 1 <= iters <= 2^24, else
+ *     QASR_ERR_PARAM); writes qasr_probe_mfma_i8_outputs() int32 values to `out` (device) and the
+ *     number of integer operations (2 per multiply-add) the launch performs to *ops (HOST). */
+qasr_status qasr_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+int32_t qasr_probe_mfma_i8_outputs(void);
+qasr_status qasr_probe_mfma_i8(int32_t iters, int32_t* out, double* ops, void* stream);
+
 /* Name of the kernel family qasr_conv1d_int8 would dispatch this descriptor to (host-only). */
 const char* qasr_conv1d_kernel_name(const qasr_conv1d_desc* d);
 

@@ -83,6 +83,12 @@ def lib():
         L.qasr_quantize.argtypes = [_vp, ctypes.c_size_t, ctypes.c_float, _vp, _vp]
         L.qasr_dequantize.restype = _i32
         L.qasr_dequantize.argtypes = [_vp, ctypes.c_size_t, ctypes.c_float, _vp, _vp]
+        L.qasr_probe_copy.restype = _i32
+        L.qasr_probe_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
+        L.qasr_probe_mfma_i8_outputs.restype = _i32
+        L.qasr_probe_mfma_i8_outputs.argtypes = []
+        L.qasr_probe_mfma_i8.restype = _i32
+        L.qasr_probe_mfma_i8.argtypes = [_i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
         L.qasr_encoder_create.restype = _i32
         L.qasr_encoder_create.argtypes = [ctypes.POINTER(_Op), _i32, _i32, ctypes.POINTER(_vp)]
         L.qasr_encoder_workspace_bytes.restype = ctypes.c_size_t
@@ -231,6 +237,26 @@ def dequantize(q, S: float, x):
     """qasr_dequantize: int8 tensor q -> float32 tensor x of the same number of elements."""
     _check(lib().qasr_dequantize(_ptr(q), q.numel(), S, _ptr(x), _stream()), "qasr_dequantize")
     return x
+
+
+def probe_copy(src, dst):
+    """qasr_probe_copy: streaming copy of the bytes of tensor src into dst (same size, a multiple of 16 bytes)."""
+    n = src.numel() * src.element_size()
+    assert n == dst.numel() * dst.element_size()
+    _check(lib().qasr_probe_copy(_ptr(src), _ptr(dst), n, _stream()), "qasr_probe_copy")
+    return dst
+
+
+def probe_mfma_outputs() -> int:
+    return int(lib().qasr_probe_mfma_i8_outputs())
+
+
+def probe_mfma_i8(iters: int, out) -> float:
+    """qasr_probe_mfma_i8: register-resident int8 matrix-core loop; returns the integer operations of the launch."""
+    assert out.numel() >= probe_mfma_outputs() and out.element_size() == 4
+    ops = ctypes.c_double(0.0)
+    _check(lib().qasr_probe_mfma_i8(iters, _ptr(out), ctypes.byref(ops), _stream()), "qasr_probe_mfma_i8")
+    return float(ops.value)
 
 
 def observe_minmax(x, minmax):

@@ -359,6 +359,24 @@ qasr_status qasr_dequantize(const int8_t* q, size_t n, float S, float* x, void* 
   return hip_status(qasr::launch_dequantize(q, n, S, x, (hipStream_t)stream));
 }
 
+qasr_status qasr_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (bytes == 0) return QASR_OK;
+  if (!src || !dst) return QASR_ERR_NULL;
+  if (bytes % 16 || (uintptr_t)src % 16 || (uintptr_t)dst % 16) return QASR_ERR_SHAPE;
+  if (bytes > ((size_t)1 << 40)) return QASR_ERR_SHAPE;
+  if (overlaps(dst, (int64_t)bytes, src, (int64_t)bytes)) return QASR_ERR_ALIAS;
+  return hip_status(qasr::launch_probe_copy(src, dst, bytes, (hipStream_t)stream));
+}
+
+int32_t qasr_probe_mfma_i8_outputs(void) { return qasr::probe_mfma_workgroups(); }
+
+qasr_status qasr_probe_mfma_i8(int32_t iters, int32_t* out, double* ops, void* stream) {
+  if (!out || !ops) return QASR_ERR_NULL;
+  if (iters < 1 || iters > (1 << 24)) return QASR_ERR_PARAM;
+  *ops = qasr::probe_mfma_ops(iters);
+  return hip_status(qasr::launch_probe_mfma(iters, out, (hipStream_t)stream));
+}
+
 qasr_status qasr_observe_minmax(const float* x, size_t n, float* minmax, void* stream) {
   if (n == 0) return QASR_OK;
   if (!x || !minmax) return QASR_ERR_NULL;

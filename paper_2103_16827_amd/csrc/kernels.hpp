@@ -46,6 +46,13 @@ hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st);
 bool conv_pipe_supported(const ConvParams& p);
 hipError_t launch_conv_pipe(const ConvParams& p, hipStream_t st);
 
+// Measured ceilings (probe.hip): a streaming copy of `bytes` (a multiple of 16) and a register-resident
+// int8 matrix-core loop of probe_mfma_ops(iters) operations that writes probe_mfma_workgroups() int32.
+hipError_t launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+int probe_mfma_workgroups();
+double probe_mfma_ops(int iters);
+hipError_t launch_probe_mfma(int iters, int32_t* out, hipStream_t st);
+
 // Quantiser (Eq. 1, b = 8; S = alpha / 127 from the host) and dequantiser (S * q) at the two ends
 // of the path; n elements, any alignment.
 hipError_t launch_quantize(const float* x, size_t n, float alpha, float S, int8_t* q, hipStream_t st);
