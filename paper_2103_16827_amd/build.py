@@ -54,6 +54,19 @@ def partial_write_hazards(asm_text: str):
     return bad
 
 
+def source_with_local_includes(src: str, seen=None) -> str:
+    """Text of a source file followed by that of every header of this directory it includes."""
+    seen = set() if seen is None else seen
+    if src in seen or not os.path.exists(src):
+        return ""
+    seen.add(src)
+    with open(src) as f:
+        text = f.read()
+    for inc in re.findall(r'#include\s+"([^"]+)"', text):
+        text += source_with_local_includes(os.path.join(os.path.dirname(src), inc), seen)
+    return text
+
+
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
@@ -64,12 +77,11 @@ def build(verbose: bool = False) -> str:
     for src in sources():
         obj = os.path.join(bdir, os.path.basename(src) + ".o")
         cmd = [hipcc, "-x", "hip", "-c", src, "-o", obj] + [f for f in HIPCC_FLAGS if f != "-shared"]
-        with open(src) as f:
-            if "_sdwa" in f.read():              # hand-written partial register writes: device assembly too
-                asm = os.path.join(bdir, os.path.basename(src) + ".gfx950.s")
-                acmd = [hipcc, "-x", "hip", "--cuda-device-only", "-S", src, "-o", asm] + \
-                       [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-Rpass-analysis=kernel-resource-usage")]
-                sdwa_sources.append((src, asm, subprocess.Popen(acmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        if "_sdwa" in source_with_local_includes(src):   # hand-written partial register writes: device assembly too
+            asm = os.path.join(bdir, os.path.basename(src) + ".gfx950.s")
+            acmd = [hipcc, "-x", "hip", "--cuda-device-only", "-S", src, "-o", asm] + \
+                   [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC", "-Rpass-analysis=kernel-resource-usage")]
+            sdwa_sources.append((src, asm, subprocess.Popen(acmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -317,3 +317,15 @@ def test_build_checks_reads_after_partial_register_writes():
     assert len(partial_write_hazards(bad)) == 1
     assert partial_write_hazards(other_reg) == []
     assert partial_write_hazards(full) == []
+
+
+def test_the_partial_write_check_covers_sources_that_include_the_asm():
+    """The byte-selected writes live in a header: the build has to find them through the includes of
+    every source that instantiates them, or the check silently covers nothing."""
+    import glob
+    from paper_2103_16827_amd.build import source_with_local_includes, CSRC
+    hit = sorted(os.path.basename(s) for s in glob.glob(os.path.join(CSRC, "*.hip"))
+                 if "_sdwa" in source_with_local_includes(s))
+    assert "pw_pipe.hip" in hit and "team.hip" in hit, hit
+    with open(os.path.join(CSRC, "pw_pipe.hip")) as f:
+        assert "_sdwa" not in f.read()          # (the reason the includes have to be followed)
