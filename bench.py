@@ -92,6 +92,20 @@ def cpu_1thread(config, max_seconds):
     return json.loads(r.stdout.strip().splitlines()[-1])
 
 
+def measured_mfma_busy(kernel, config):
+    """Fraction of the kernels' duration in which the matrix pipes were busy, by the hardware counters
+    (profiles/<kernel>_config<N>_mfma_busy.txt, whose header gives the commands); None without one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_config{config}_mfma_busy.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith(f"mfma_busy_{kernel}:"):
+                    return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -294,6 +308,8 @@ def main():
     roofline["frac_of_measured_ceiling"] = achieved / (ceilings["hbm_copy_GBs"] if roofline["bound"] == "hbm"
                                                        else ceilings["int8_mfma_TOPs"])
     roofline["traffic"] = measured_traffic(dom, args.config)
+    if roofline["bound"] == "mfma":
+        roofline["mfma_busy_by_counters"] = measured_mfma_busy(dom, args.config)
     roofline["avg_launch_us"] = avg_ms * 1e3
     roofline["launches_per_step"] = d["launches"]
     roofline["share_of_device_time"] = d["ms"] / float(op_ms.sum())
