@@ -218,40 +218,9 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
     const int mt = e / NT, nt = e % NT;
     return reinterpret_cast<uint32_t*>(stage0 + par * (ROWS * 128) + nt * 2048 + (sbase ^ (uint32_t)(mt << 4)));
   };
-  // Without a residual operand the clamp can come before the shift (the bounds shifted left
-  // instead: [0, 128 2^sh - 1], which needs sh <= 23), and shift and byte insertion are one
-  // instruction (a shift whose result goes to byte i of the destination, the other bytes kept):
-  // four stages,  T0 h = mulhi(acc, m)   T1 h += rnd   T2 h = clamp(h, 0, hib)   T3 word.byte[i] = h >> sh,
-  // two elements in flight (element x in ph[x & 1]), two instructions per step.
-  // (On this chip a vector instruction may not read a register in the cycle after an instruction
-  // wrote part of it through a byte selector; the compiler cannot see inside the asm statements.
-  // Here the byte insertions into `pword` are at least three vector instructions apart, and the
-  // only other reader of `pword` is the LDS store.  The same trick on four values back to back
-  // gives wrong bytes: tried in the unpipelined epilogues, not kept.)
-  int32_t hib[NT];
-  auto shift_into_byte = [&](int i, int32_t shv, int32_t hv) __attribute__((always_inline)) {
-    if (i == 0) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(pword) : "v"(shv), "v"(hv));
-    if (i == 1) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(pword) : "v"(shv), "v"(hv));
-    if (i == 2) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_2 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(pword) : "v"(shv), "v"(hv));
-    if (i == 3) asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_3 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD" : "+v"(pword) : "v"(shv), "v"(hv));
-  };
-  // (RES false: a layer without residual operand takes the four-stage form)
+  // (RES false: no residual byte is added at S3; the stages stay the same)
   auto step = [&](int par, int t, auto res_tag) __attribute__((always_inline)) {
     constexpr bool RES = decltype(res_tag)::value;
-    if constexpr (!RES) {
-      const int y0 = t >> 1, y1 = y0 - 1;                     // the elements at stages (T0|T1), (T2|T3)
-      if ((t & 1) == 0) {
-        if (y0 < NE) ph[y0 & 1] = mulhi_i32(acc[par][(y0 >> 2) / NT][(y0 >> 2) % NT][y0 & 3], mc[(y0 >> 2) % NT]);
-        if (y1 >= 0 && y1 < NE) ph[y1 & 1] = med3_i32(ph[y1 & 1], 0, hib[(y1 >> 2) % NT]);
-      } else {
-        if (y0 < NE) ph[y0 & 1] += rnd[(y0 >> 2) % NT];
-        if (y1 >= 0 && y1 < NE) {
-          shift_into_byte(y1 & 3, sh[(y1 >> 2) % NT], ph[y1 & 1]);
-          if ((y1 & 3) == 3) *stage_word(par, y1 >> 2) = pword;
-        }
-      }
-      return;
-    }
     const int x0 = t >> 1, x1 = x0 - 1, x2 = x0 - 2;        // the elements at stages (S0|S1), (S2|S3), (S4|S5)
     if ((t & 1) == 0) {
       if (x0 < NE) {
@@ -387,7 +356,7 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
     }
     if (PREV) {
 #pragma unroll
-      for (int t = 8 * NB; t < (RES ? NSTEPS : NSTEPS - 2); ++t) step(par ^ 1, t, res_tag);     // the last elements drain
+      for (int t = 8 * NB; t < NSTEPS; ++t) step(par ^ 1, t, res_tag);     // the last elements drain
       store_rows(ps - 1, par ^ 1);                 // (the caller counts these requests)
     }
   };
@@ -409,14 +378,13 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
     for (int nt = 0; nt < NT; ++nt) {
       mc[nt] = *reinterpret_cast<const int32_t*>(c + nt * 192 + 64);
       s_[nt] = *reinterpret_cast<const int32_t*>(c + nt * 192 + 128);
-      fast = fast && s_[nt] >= 33 && s_[nt] <= 55;      // (the four-stage epilogue shifts its clamp bound left by s - 32)
+      fast = fast && s_[nt] >= 33;
     }
     const bool all_fast = __builtin_amdgcn_readfirstlane((int)__all(fast)) != 0;   // wave-uniform, and known to be
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       sh[nt] = all_fast ? s_[nt] - 32 : s_[nt];
       rnd[nt] = all_fast ? 1 << ((s_[nt] - 33) & 31) : 0;
-      hib[nt] = all_fast ? (128 << (sh[nt] & 31)) - 1 : 0;
     }
     if (all_fast && p.relu && !has_act && ps + 1 < P) {
       pending = true;
