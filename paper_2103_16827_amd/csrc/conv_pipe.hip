@@ -43,6 +43,8 @@ struct CpGeom {
   int rows;           // LDS rows (input frames incl. halo, rounded to 4)
   int kchunks;        // Cin / 64
   int co16n;          // ceil(Cout / 16)
+  int tiles;          // B * n_tt * n_co
+  int per_xcd;        // ceil(tiles / 8): tiles of one XCD (the grid is 8 * per_xcd workgroups)
 };
 
 template <int MT, int NT>
@@ -53,11 +55,20 @@ __global__ __launch_bounds__(256) void conv_pipe_kernel(ConvParams p, CpGeom g) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, gi = lane >> 4;
 
-  int id = blockIdx.x;
-  const int co_tile = id % g.n_co;
-  id /= g.n_co;
-  const int t_tile = id % g.n_tt;
-  const int b = id / g.n_tt;
+  // Workgroup -> tile.  Consecutive workgroups go round-robin to the 8 XCDs, each with an L2 of its
+  // own, and every workgroup streams the whole weight slice of its channel tile: so the tiles are
+  // numbered channel tile first (slowest), then batch item, then frame tile, and XCD x takes the
+  // contiguous run [x per_xcd, (x + 1) per_xcd) of that order.  An XCD then touches one channel tile,
+  // two where its run crosses a boundary, instead of all of them, and its workgroups, which start
+  // together and step through the same (chunk, tap) sequence, share each weight line while it is
+  // in that L2; neighbouring frame tiles (shared halo lines) stay on one XCD as well.
+  // (per_xcd == 0, a tuning override: the plain order, tile = workgroup index, for comparisons)
+  const int v = g.per_xcd ? (int)(blockIdx.x & 7) * g.per_xcd + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  if (v >= g.tiles) return;                         // whole workgroup, before any barrier
+  const int bt = v % (g.tiles / g.n_co);            // (b, t_tile) of the tile
+  const int co_tile = v / (g.tiles / g.n_co);
+  const int t_tile = bt % g.n_tt;
+  const int b = bt / g.n_tt;
 
   const int t0 = t_tile * TM;                       // first output frame of the tile
   const int f0 = t0 * p.stride - p.pl;              // first input frame the tile reads
@@ -287,7 +298,7 @@ bool pick(const ConvParams& p, int& MT, int& NT) {
       if (rows > kMaxRows || (int64_t)p.Cin * p.Tin > 0x7fffffffLL) continue;
       const int64_t n_tt = (p.Tout + TM - 1) / TM, n_co = (p.Cout + 64 * nt - 1) / (64 * nt);
       const int64_t blocks = (int64_t)p.B * n_tt * n_co;
-      if (blocks > 0x7fffffffLL) continue;
+      if (blocks > 0x7ffffff0LL) continue;
       // halo read and transposed per tile, relative to the products
       const double cost = step_cycles(mt, nt, blocks) * (1.0 + 0.25 / mt);
       if (cost < best * 0.999) { best = cost; MT = mt; NT = nt; found = true; }
@@ -305,7 +316,9 @@ hipError_t launch_t(const ConvParams& p, hipStream_t st) {
   g.kchunks = p.Cin / 64;
   g.co16n = (p.Cout + 15) / 16;
   const int64_t blocks = (int64_t)p.B * g.n_tt * g.n_co;
-  return launch_kernel(conv_pipe_kernel<MT, NT>, dim3((unsigned)blocks), dim3(256),
+  g.tiles = (int)blocks;
+  g.per_xcd = tuning().cp_plain_order ? 0 : (int)((blocks + 7) / 8);
+  return launch_kernel(conv_pipe_kernel<MT, NT>, dim3((unsigned)(g.per_xcd ? 8 * g.per_xcd : (int)blocks)), dim3(256),
                        (size_t)2 * g.rows * kXS, st, p, g);
 }
 

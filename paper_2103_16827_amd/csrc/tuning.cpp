@@ -19,6 +19,7 @@ Tuning read_env() {
   t.no_pw_pipe = getenv("QASR_NO_PW_PIPE") != nullptr;
   t.no_conv_pipe = getenv("QASR_NO_CONV_PIPE") != nullptr;
   t.team = getenv("QASR_TEAM") != nullptr;
+  t.cp_plain_order = getenv("QASR_CP_PLAIN_ORDER") != nullptr;
   if (const char* e = getenv("QASR_PWP_MT")) t.pwp_mt = atoi(e);
   if (const char* e = getenv("QASR_PWP_SPLIT")) t.pwp_split = atoi(e);
   if (const char* e = getenv("QASR_DWP")) {

@@ -6,6 +6,7 @@
 //   QASR_DWP = "R,S"                        dw_pipe: rows per iteration, batch splits
 //   QASR_DW_R                               dw_mfma: strips per wave
 //   QASR_CP_TILE = "MT,NT"                  conv_pipe: tile
+//   QASR_CP_PLAIN_ORDER                     conv_pipe: tile = workgroup index (no per-XCD runs of the channel-major order)
 //   QASR_PWT_MT                             pw_tile: groups per tile
 //   QASR_TEAM                               encoder: plan runs of layers for the persistent team kernel
 //                                           (experimental, off unless set)
@@ -14,7 +15,7 @@
 namespace qasr {
 
 struct Tuning {
-  bool no_pw_pipe = false, no_conv_pipe = false, team = false;
+  bool no_pw_pipe = false, no_conv_pipe = false, team = false, cp_plain_order = false;
   int pwp_mt = 0, pwp_split = 0;
   int dwp_r = 0, dwp_s = 0;
   int dw_r = 0;
