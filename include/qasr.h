@@ -267,8 +267,25 @@ typedef struct qasr_encoder qasr_encoder; /* opaque host object */
 qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slots,
                                 qasr_encoder** out);
 
-/* Bytes of workspace qasr_encoder_forward needs (all slots except the input and the output,
- * each rounded up to 256 bytes).  Known at create time because every shape and scale of the
+/* Which memory the values of the slots live in is the library's choice (slots name values, not
+ * addresses): at create time every op's output is given the workspace buffer that has been free
+ * longest among those that none of the QASR_SLOT_DEPTH (environment, default 4, 0..16) ops before
+ * it read or wrote, a new buffer if there is none.  On this chip a kernel that writes memory which
+ * the kernel right before it read under another workgroup-to-XCD mapping runs microseconds
+ * longer; the two-slot ping-pong of a plain layer chain does that in every layer (measured: the
+ * QuartzNet-15x5 shape at batch 32 takes 1.77 ms per forward with the slots as buffers, 1.49 ms
+ * with depth 4).  Depth 0 keeps the caller's slots as the buffers.  The workspace grows by up to
+ * `depth` buffers.
+ *   qasr_plan_slot_buffers: the same plan on bare wiring (HOST only, no device needed; for tests and
+ *   diagnostics): in/res/out_slot[n_ops] as in qasr_op (res -1 for none) -> in/res/out_buf[n_ops]
+ *   (buffer 0 is the network input) and the number of buffers; QASR_ERR_PARAM for wiring that
+ *   qasr_encoder_create would reject or depth outside 0..16. */
+qasr_status qasr_plan_slot_buffers(const int32_t* in_slot, const int32_t* res_slot, const int32_t* out_slot,
+                                   int32_t n_ops, int32_t n_slots, int32_t depth, int32_t* in_buf,
+                                   int32_t* res_buf, int32_t* out_buf, int32_t* n_buffers);
+
+/* Bytes of workspace qasr_encoder_forward needs (all buffers of the plan above except the input
+ * and the output, each rounded up to 256 bytes).  Known at create time because every shape and scale of the
  * integer model is static (Sec. 2.1: static quantisation, nothing is sized at inference).  HOST only. */
 size_t qasr_encoder_workspace_bytes(const qasr_encoder* e);
 

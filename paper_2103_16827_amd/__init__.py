@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     conv1d_kernel_name, Encoder, EncoderGraph, ConvDesc, FLAG_RELU, FLAG_W_PACKED, status_string,
     quantize, dequantize, IExp, Act, ACT_SIGMOID, ACT_SWISH, ACT_GLU, iexp_init, make_act, act_int8,
     softmax_int32, conv1d_int8_multi, MAX_RESIDUALS, observe_minmax, dyadic_from_scale, fold_bn_quantize,
-    tuning_reload, static_workspace_bytes, probe_copy, probe_mfma_i8, probe_mfma_outputs,
+    tuning_reload, static_workspace_bytes, probe_copy, probe_mfma_i8, probe_mfma_outputs, plan_slot_buffers,
 )

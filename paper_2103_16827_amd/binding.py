@@ -83,6 +83,8 @@ def lib():
         L.qasr_quantize.argtypes = [_vp, ctypes.c_size_t, ctypes.c_float, _vp, _vp]
         L.qasr_dequantize.restype = _i32
         L.qasr_dequantize.argtypes = [_vp, ctypes.c_size_t, ctypes.c_float, _vp, _vp]
+        L.qasr_plan_slot_buffers.restype = _i32
+        L.qasr_plan_slot_buffers.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _vp, _vp, _vp, ctypes.POINTER(_i32)]
         L.qasr_probe_copy.restype = _i32
         L.qasr_probe_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
         L.qasr_probe_mfma_i8_outputs.restype = _i32
@@ -237,6 +239,16 @@ def dequantize(q, S: float, x):
     """qasr_dequantize: int8 tensor q -> float32 tensor x of the same number of elements."""
     _check(lib().qasr_dequantize(_ptr(q), q.numel(), S, _ptr(x), _stream()), "qasr_dequantize")
     return x
+
+
+def plan_slot_buffers(in_slot, res_slot, out_slot, n_slots: int, depth: int):
+    """qasr_plan_slot_buffers (host only): (in_buf, res_buf, out_buf, n_buffers) for bare slot wiring."""
+    n = len(in_slot)
+    A = _i32 * n
+    ib, rb, ob, nb = A(), A(), A(), _i32(0)
+    _check(lib().qasr_plan_slot_buffers(A(*in_slot), A(*res_slot), A(*out_slot), n, n_slots, depth, ib, rb, ob,
+                                        ctypes.byref(nb)), "qasr_plan_slot_buffers")
+    return list(ib), list(rb), list(ob), int(nb.value)
 
 
 def probe_copy(src, dst):

@@ -472,6 +472,118 @@ qasr_status qasr_softmax_int32(const qasr_iexp* e, const int32_t* x, int64_t row
   return hip_status(qasr::launch_softmax(act_params(0, 0, 1, *e), x, rows, L, y, (hipStream_t)stream));
 }
 
+// ---- buffers for the activation slots.  The caller's slot numbers say which op reads what; which
+// memory a value lives in is the library's choice.  It matters: a kernel that writes a buffer which
+// the kernel right before it READ runs 3-4 us longer (measured on single layers and on the whole
+// encoder: the lines are still held by the L2s of the XCDs that read them, under another
+// workgroup-to-XCD mapping, and every write has to displace them), and the two-slot ping-pong of a
+// plain layer chain does exactly that in every layer.  So the values are renamed onto physical
+// buffers: the output of op i takes the buffer that has been free longest among those that none of
+// the `depth` ops before it touched, a new one if there is none (depth + 2 buffers for a plain
+// chain).  depth 0 keeps the caller's slots as the buffers.
+struct SlotPlan {
+  std::vector<int32_t> in, res, out;                 // physical buffer per op (0 = the network input)
+  std::vector<std::vector<int32_t>> more;
+  std::vector<size_t> bytes;                         // per physical buffer (index 0 unused)
+};
+
+struct SlotWire {                                    // what one op reads and writes, in the caller's slots
+  int32_t in, res, out;
+  std::vector<int32_t> more;
+  size_t bytes;                                      // of the value it writes (0: goes to the caller's output)
+};
+
+static void plan_slots(const std::vector<SlotWire>& ops, int32_t n_slots, int depth, SlotPlan& pl) {
+  const int32_t n_ops = (int32_t)ops.size();
+  pl.in.resize(n_ops); pl.res.assign(n_ops, -1); pl.out.resize(n_ops); pl.more.assign(n_ops, {});
+  if (depth <= 0) {
+    pl.bytes.assign(n_slots, 0);
+    for (int32_t i = 0; i < n_ops; ++i) {
+      pl.in[i] = ops[i].in; pl.res[i] = ops[i].res; pl.out[i] = ops[i].out;
+      pl.more[i] = ops[i].more;
+      if (ops[i].bytes > pl.bytes[ops[i].out]) pl.bytes[ops[i].out] = ops[i].bytes;
+    }
+    return;
+  }
+  // values: 0 is the network input, i + 1 what op i writes
+  std::vector<int32_t> cur(n_slots, -1), last_use(n_ops + 1, -1);
+  cur[0] = 0;
+  std::vector<std::vector<int32_t>> reads(n_ops);
+  for (int32_t i = 0; i < n_ops; ++i) {
+    const SlotWire& o = ops[i];
+    reads[i].push_back(cur[o.in]);
+    if (o.res >= 0) reads[i].push_back(cur[o.res]);
+    for (int32_t sl : o.more) reads[i].push_back(cur[sl]);
+    for (int32_t v : reads[i]) last_use[v] = i;
+    cur[o.out] = i + 1;
+  }
+  std::vector<int32_t> buf_of(n_ops + 1, -1), holders, free_q;
+  buf_of[0] = 0;
+  pl.bytes.assign(1, 0);
+  std::vector<std::vector<int32_t>> touched(n_ops);
+  for (int32_t i = 0; i < n_ops; ++i) {
+    for (size_t h = 0; h < holders.size();) {              // values nobody reads from op i on
+      if (last_use[holders[h]] < i) {
+        free_q.push_back(buf_of[holders[h]]);
+        holders.erase(holders.begin() + (long)h);
+      } else {
+        ++h;
+      }
+    }
+    auto recent = [&](int32_t b) {
+      for (int32_t j = i - 1; j >= 0 && j >= i - depth; --j)
+        for (int32_t t : touched[j])
+          if (t == b) return true;
+      return false;
+    };
+    int32_t b = -1;
+    for (size_t q = 0; q < free_q.size(); ++q)
+      if (!recent(free_q[q])) {
+        b = free_q[q];
+        free_q.erase(free_q.begin() + (long)q);
+        break;
+      }
+    if (b < 0) {
+      b = (int32_t)pl.bytes.size();
+      pl.bytes.push_back(0);
+    }
+    buf_of[i + 1] = b;
+    pl.out[i] = b;
+    holders.push_back(i + 1);
+    if (ops[i].bytes > pl.bytes[b]) pl.bytes[b] = ops[i].bytes;
+    size_t k = 0;
+    pl.in[i] = buf_of[reads[i][k++]];
+    if (ops[i].res >= 0) pl.res[i] = buf_of[reads[i][k++]];
+    for (; k < reads[i].size(); ++k) pl.more[i].push_back(buf_of[reads[i][k]]);
+    touched[i].push_back(b);
+    for (int32_t v : reads[i]) touched[i].push_back(buf_of[v]);
+  }
+}
+
+qasr_status qasr_plan_slot_buffers(const int32_t* in_slot, const int32_t* res_slot, const int32_t* out_slot,
+                                   int32_t n_ops, int32_t n_slots, int32_t depth, int32_t* in_buf,
+                                   int32_t* res_buf, int32_t* out_buf, int32_t* n_buffers) {
+  if (!in_slot || !res_slot || !out_slot || !in_buf || !res_buf || !out_buf || !n_buffers) return QASR_ERR_NULL;
+  if (n_ops < 1 || n_slots < 2) return QASR_ERR_SHAPE;
+  if (depth < 0 || depth > 16) return QASR_ERR_PARAM;
+  std::vector<char> live(n_slots, 0);
+  live[0] = 1;
+  std::vector<SlotWire> w(n_ops);
+  for (int32_t i = 0; i < n_ops; ++i) {
+    if (in_slot[i] < 0 || in_slot[i] >= n_slots || out_slot[i] < 1 || out_slot[i] >= n_slots || res_slot[i] < -1 ||
+        res_slot[i] >= n_slots || out_slot[i] == in_slot[i] || out_slot[i] == res_slot[i])
+      return QASR_ERR_PARAM;
+    if (!live[in_slot[i]] || (res_slot[i] >= 0 && !live[res_slot[i]])) return QASR_ERR_PARAM;
+    live[out_slot[i]] = 1;
+    w[i] = SlotWire{in_slot[i], res_slot[i], out_slot[i], {}, (size_t)1};
+  }
+  SlotPlan pl;
+  plan_slots(w, n_slots, depth, pl);
+  for (int32_t i = 0; i < n_ops; ++i) { in_buf[i] = pl.in[i]; res_buf[i] = pl.res[i]; out_buf[i] = pl.out[i]; }
+  *n_buffers = (int32_t)pl.bytes.size();
+  return QASR_OK;
+}
+
 qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slots, qasr_encoder** out) {
   if (!ops || !out) return QASR_ERR_NULL;
   if (n_ops < 1 || n_slots < 2) return QASR_ERR_SHAPE;
@@ -480,7 +592,6 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
   // ---- validation: host only, no HIP call yet
   struct SlotState { bool live = false; int32_t C = 0, T = 0; };
   std::vector<SlotState> slot(n_slots);
-  std::vector<size_t> slot_bytes(n_slots, 0);
   size_t packed_bytes = 0;
   for (int32_t i = 0; i < n_ops; ++i) {
     const qasr_op& o = ops[i];
@@ -529,19 +640,30 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     slot[o.out_slot].live = true;
     slot[o.out_slot].C = o.d.Cout;
     slot[o.out_slot].T = Tout;
-    const size_t bytes = (size_t)o.d.B * o.d.Cout * Tout;
-    if (bytes > slot_bytes[o.out_slot]) slot_bytes[o.out_slot] = bytes;
     if (has_packed_form(&o.d)) packed_bytes += round256(packed_bytes_of(&o.d));
     if (o.act && o.act->kind != QASR_ACT_GLU) packed_bytes += 256;   // room for a fused activation's table
   }
 
   qasr_encoder* e = new (std::nothrow) qasr_encoder();
   if (!e) return QASR_ERR_HIP;
-  e->slot_off.assign(n_slots, 0);
+  SlotPlan plan;
+  {
+    std::vector<SlotWire> wires(n_ops);
+    for (int32_t i = 0; i < n_ops; ++i) {
+      const qasr_op& o = ops[i];
+      wires[i] = SlotWire{o.in_slot, o.res_slot, o.out_slot,
+                          std::vector<int32_t>(o.more_res_slots, o.more_res_slots + o.n_more_res),
+                          i + 1 == n_ops ? (size_t)0   // (the last op writes the caller's output)
+                                         : (size_t)o.d.B * o.d.Cout * (size_t)out_len64(&o.d)};
+    }
+    plan_slots(wires, n_slots, qasr::tuning().slot_depth, plan);
+  }
+  const int32_t n_bufs = (int32_t)plan.bytes.size();
+  e->slot_off.assign(n_bufs, 0);
   size_t off = 0;
-  for (int32_t sidx = 1; sidx < n_slots; ++sidx) {
+  for (int32_t sidx = 1; sidx < n_bufs; ++sidx) {
     e->slot_off[sidx] = off;
-    off += round256(slot_bytes[sidx]);
+    off += round256(plan.bytes[sidx]);
   }
   e->ws_bytes = off;
   e->in_elems = (size_t)ops[0].d.B * slot[0].C * slot[0].T;
@@ -561,7 +683,7 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     const qasr_op& o = ops[i];
     qasr_encoder::Op& op = e->ops[i];
     op.d = o.d;
-    op.in_slot = o.in_slot; op.res_slot = o.res_slot; op.out_slot = o.out_slot;
+    op.in_slot = plan.in[i]; op.res_slot = plan.res[i]; op.out_slot = plan.out[i];   // (buffers, not the caller's slots)
     const int8_t* w = o.w;
     if (has_packed_form(&o.d)) {
       int8_t* wp = e->packed + poff;
@@ -577,7 +699,7 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     op.p = make_params(&op.d, nullptr, w, o.bias, o.m, o.s, nullptr, nullptr);
     op.n_more_res = o.n_more_res;
     op.p.n_res_more = o.n_more_res;
-    for (int32_t r = 0; r < o.n_more_res; ++r) op.more_res_slots[r] = o.more_res_slots[r];
+    for (int32_t r = 0; r < o.n_more_res; ++r) op.more_res_slots[r] = plan.more[i][r];
     op.kernel = pick_kernel(op.p);
     if (o.act) {
       op.has_act = true;
@@ -601,7 +723,7 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
     }
   }
   {
-    const qasr_status ts = plan_team_runs(e, n_slots);
+    const qasr_status ts = plan_team_runs(e, n_bufs);
     if (ts != QASR_OK) {
       qasr_encoder_destroy(e);
       return ts;

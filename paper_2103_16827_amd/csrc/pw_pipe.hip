@@ -43,7 +43,16 @@ __global__ __launch_bounds__(512) void pw_pipe_kernel(ConvParams p, PwpGeom g) {
   pw_pipe_tile<MT, KCH, ACT, false>(p, g, blockIdx.x, xs, (int)threadIdx.x);
 }
 
-struct Choice { int MT, KCH, splits; };
+// The lean form: one pass per workgroup, two workgroups per compute unit (four waves per SIMD:
+// at most 128 registers each).
+template <int MT, int KCH>
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(4, 4)))
+void pw_lean_kernel(ConvParams p, PwpGeom g) {
+  extern __shared__ __align__(128) unsigned char xs[];
+  pw_pipe_tile<MT, KCH, false, false, 2, true>(p, g, blockIdx.x, xs, (int)threadIdx.x);
+}
+
+struct Choice { int MT, KCH, splits; bool lean; };
 
 size_t lds_bytes(int KCH) { return KCH == 4 ? lds_bytes_c<4>() : lds_bytes_c<8>(); }   // (8 chunks at most are resident)
 
@@ -98,10 +107,14 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   if (passes & (passes - 1)) {                              // (splits run over powers of two)
     if (c.KCH > 8) return false;
   }
+  // lean form (experimental, tuning only): plain layers whose tile stays resident, every pass a
+  // workgroup of its own
+  c.lean = tuning().pw_lean && !p.res && !p.act_lut && c.KCH <= 8 && p.Cout % (8 * ROWS) == 0;
+  if (c.lean) c.splits = passes;
   {                                                       // tuning overrides
     const int mt = tuning().pwp_mt, sp = tuning().pwp_split;
     if (mt >= 4 && mt <= kMaxMT) c.MT = mt;
-    if (sp >= 1 && passes % sp == 0 && (sp == 1 || p.Cout % (8 * ROWS) == 0) && c.KCH <= 8) c.splits = sp;
+    if (!c.lean && sp >= 1 && passes % sp == 0 && (sp == 1 || p.Cout % (8 * ROWS) == 0) && c.KCH <= 8) c.splits = sp;
   }
   return lds_bytes(c.KCH) <= 160 * 1024;
 }
@@ -117,11 +130,32 @@ hipError_t launch_a(const ConvParams& p, int splits, hipStream_t st) {
   g.tiles_per_xcd = (g.tiles + 7) / 8;
   g.splits = splits;
   g.pps = g.passes / splits;
+  g.nopipe = tuning().pwp_nopipe ? 1 : 0;
   static std::atomic<uint64_t> lds_raised{0};   // per instantiation, a bit per device
   if (const hipError_t e = ensure_max_dynamic_lds((const void*)pw_pipe_kernel<MT, KCH, ACT>, lds_raised); e != hipSuccess)
     return e;
   return launch_kernel(pw_pipe_kernel<MT, KCH, ACT>, dim3((unsigned)(8 * g.tiles_per_xcd * g.splits)), dim3(512),
                        (size_t)lds_bytes_c<KCH>(), st, p, g);
+}
+
+template <int MT, int KCH>
+hipError_t launch_lean(const ConvParams& p, hipStream_t st) {
+  PwpGeom g;
+  g.gpr = p.Tin / 16;
+  g.G = p.B * g.gpr;
+  g.passes = p.Cout / (8 * ROWS);
+  g.co16n = (p.Cout + 15) / 16;
+  g.tiles = (g.G + MT - 1) / MT;
+  g.tiles_per_xcd = (g.tiles + 7) / 8;
+  g.splits = g.passes;
+  g.pps = 1;
+  g.nopipe = 1;
+  static std::atomic<uint64_t> lds_raised{0};
+  if (const hipError_t e = ensure_max_dynamic_lds((const void*)pw_lean_kernel<MT, KCH>, lds_raised, lds_bytes_lean_c<KCH>());
+      e != hipSuccess)
+    return e;
+  return launch_kernel(pw_lean_kernel<MT, KCH>, dim3((unsigned)(8 * g.tiles_per_xcd * g.splits)), dim3(512),
+                       (size_t)lds_bytes_lean_c<KCH>(), st, p, g);
 }
 
 template <int MT, int KCH>
@@ -139,6 +173,10 @@ bool pw_pipe_supported(const ConvParams& p) {
 hipError_t launch_pw_pipe(const ConvParams& p, hipStream_t st) {
   Choice c;
   if (!pick(p, c, num_cus())) return hipErrorInvalidValue;
+#define QASR_CASE(M, K) if (c.lean && c.MT == M && c.KCH == K) return launch_lean<M, K>(p, st);
+  QASR_CASE(4, 4) QASR_CASE(5, 4) QASR_CASE(6, 4) QASR_CASE(7, 4)
+  QASR_CASE(4, 8) QASR_CASE(5, 8) QASR_CASE(6, 8) QASR_CASE(7, 8)
+#undef QASR_CASE
 #define QASR_CASE(M, K) if (c.MT == M && c.KCH == K) return launch_t<M, K>(p, c.splits, st);
   QASR_CASE(4, 4) QASR_CASE(5, 4) QASR_CASE(6, 4) QASR_CASE(7, 4)
   QASR_CASE(4, 8) QASR_CASE(5, 8) QASR_CASE(6, 8) QASR_CASE(7, 8)

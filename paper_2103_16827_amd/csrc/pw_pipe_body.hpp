@@ -30,6 +30,7 @@ struct PwpGeom {
   int co16n;    // ceil(Cout / 16)
   int tiles, tiles_per_xcd;
   int splits, pps;   // workgroups per tile (each takes pps consecutive passes of the output channels)
+  int nopipe;        // tuning: every pass does its epilogue right after its own products
 };
 
 __device__ __forceinline__ v2i lds_read_tr8(const unsigned char* p) {
@@ -45,6 +46,11 @@ __device__ __forceinline__ v2i lds_read_tr8(const unsigned char* p) {
 //      [8 waves][256 B] the fused activation's table (one copy per wave: no barrier needed)
 template <int KCH>
 constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS * 128 + 8 * MAXP * NT * 3 * 64 + 8 * 256; }
+// The lean form (see LEAN below): the activation tile and one 16-row staging block per wave, which
+// also holds the wave's constants until the epilogue starts; at 512 input channels exactly half
+// of a compute unit's LDS, so that two workgroups are resident together.
+template <int KCH>
+constexpr int lds_bytes_lean_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 16 * 128; }
 
 // ACT: a unary activation's table is applied after the clamp (an instantiation of its own: the
 // plain layers keep their code as it is)
@@ -53,12 +59,18 @@ constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS *
 // by other workgroups of this XCD, so they are loaded at device scope (past the vector cache, out of
 // the XCD's L2), and the output rows are stored write-back (the next layer reads them from that L2).
 // LOOK: weight chunks requested ahead of the one being multiplied (a ring of LOOK x NT x 4 registers).
-template <int MT, int KCH, bool ACT, bool TEAM, int LOOK = kLookW>
+// LEAN: exactly one pass per workgroup (the launcher gives every pass of a tile a workgroup of its
+// own), one accumulator set, no residual operand, no fused activation, staging of 16 rows at a
+// time: half the registers and half the LDS, so that two workgroups share a compute unit and each
+// SIMD has four waves to pick instructions from; the epilogue of one workgroup then overlaps the
+// products of the other by chance instead of by construction.
+template <int MT, int KCH, bool ACT, bool TEAM, int LOOK = kLookW, bool LEAN = false>
 __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom& g, unsigned vblock,
                                              unsigned char* const xs, int tid) {
   constexpr int NB = MT * NT;                     // epilogue blocks of a pass
   static_assert(KCH == 4 || KCH == 8 || KCH == 16 || KCH == 32, "instantiated input widths");
   static_assert(KCH % LOOK == 0, "ring slot of a chunk");
+  static_assert(!LEAN || (!ACT && !TEAM && KCH <= 8), "the lean form: plain layers, resident tile");
 
   // `tid`: the thread's index in the workgroup (threadIdx.x).
   // (inside the team kernel's layer loop: keeps everything derived from the thread id inside the
@@ -80,7 +92,7 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
   const int g0 = tile * MT;
   // passes in which this wave has channels (>= 1: Cout >= 256, and a multiple of 256 when split);
   // it leaves after them
-  const int P = min(g.pps, min(g.passes, (p.Cout - wave * ROWS + 8 * ROWS - 1) / (8 * ROWS)) - pb);
+  const int P = LEAN ? 1 : min(g.pps, min(g.passes, (p.Cout - wave * ROWS + 8 * ROWS - 1) / (8 * ROWS)) - pb);
 
   // lane -> (row lane/8 of a block of 8 rows, slot lane%8); the unit in that slot, slot ^ (row & 7),
   // is the same for every block of 8 rows: one lane -> unit map for activation loads, residual
@@ -91,9 +103,11 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
   const int b_l = gq_l / g.gpr, t16_l = gq_l - b_l * g.gpr;
   const int64_t yoff_l = (int64_t)b_l * p.ybs + 16 * t16_l;       // of this lane's unit
   constexpr int XCH = KCH < 8 ? KCH : 8;          // activation chunks resident in LDS
-  unsigned char* const stage0 = xs + XCH * 8192 + wave * (2 * ROWS * 128);
-  unsigned char* const cst0 = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
-  const bool has_res = p.res != nullptr;
+  unsigned char* const stage0 = xs + XCH * 8192 + wave * (LEAN ? 16 * 128 : 2 * ROWS * 128);
+  // (lean: the constants of the one pass sit in the wave's staging block, 384 of its 2048 bytes, and
+  // are all in registers before the first staged word is written)
+  unsigned char* const cst0 = LEAN ? stage0 : xs + XCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
+  const bool has_res = !LEAN && p.res != nullptr;
   unsigned char* const lutw = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + 8 * (MAXP * NT * 3 * 64) + wave * 256;
   constexpr bool has_act = ACT;                     // a unary activation follows the clamp
 
@@ -181,14 +195,14 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
   const int32_t hi127 = 127;
   const uint32_t y_lane = u_ok ? (uint32_t)yoff_l + (uint32_t)(lane >> 3) * (uint32_t)p.Tout : 0xfffffff0u;
 
-  v4i acc[2][MT][NT];
+  v4i acc[LEAN ? 1 : 2][MT][NT];
   int32_t mc[NT], sh[NT], rnd[NT];                // rescale constants of the pass whose epilogue is pending
 
   // one epilogue block: lane (n, gi) holds frames 16 mt + 4 gi + (0..3) of channel 16 nt + n
   auto block = [&](int par, int e, auto fast_tag, auto res_tag) __attribute__((always_inline)) {
     constexpr bool FAST = decltype(fast_tag)::value, RES = decltype(res_tag)::value;
     const int mt = e / NT, nt = e % NT;
-    uint32_t* const sp = reinterpret_cast<uint32_t*>(stage0 + par * (ROWS * 128) + nt * 2048 + (sbase ^ (uint32_t)(mt << 4)));
+    uint32_t* const sp = reinterpret_cast<uint32_t*>(stage0 + (LEAN ? 0 : par * (ROWS * 128) + nt * 2048) + (sbase ^ (uint32_t)(mt << 4)));
     const uint32_t rw = RES ? *sp : 0u;
     const v4i av = acc[par][mt][nt];
     const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
@@ -254,9 +268,37 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
       __builtin_amdgcn_raw_buffer_store_b128(ov, yrs, off, 0, TEAM ? 0 : kStoreThrough);
     }
   };
+  // lean: the 16 rows of column block nt out of the wave's one staging block
+  auto store_rows_lean = [&](int ps, int nt) __attribute__((always_inline)) {
+    const int co_w = ((pb + ps) * 8 + wave) * ROWS;
+    const __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(
+        p.y + (int64_t)co_w * p.Tout, 0, 0x7ffffff0, 0x00027000);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int it = 2 * nt + h;
+      const v4i o = *reinterpret_cast<const v4i*>(stage0 + h * 1024 + lane * 16);
+      const bool ok = u_ok && co_w + 8 * it + (lane >> 3) < p.Cout;
+      const v4u ov = {(unsigned)o.x, (unsigned)o.y, (unsigned)o.z, (unsigned)o.w};
+      const uint32_t off = ok ? y_lane + (uint32_t)(8 * it) * (uint32_t)p.Tout : 0xfffffff0u;
+      __builtin_amdgcn_raw_buffer_store_b128(ov, yrs, off, 0, kStoreThrough);
+    }
+  };
   constexpr int STORE_REQS = 2 * NT;              // requests of one store_rows
   // the epilogue of pass ps on its own
   auto epilogue_alone = [&](int ps, int par, auto fast_tag) __attribute__((always_inline)) {
+    if constexpr (LEAN) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          block(par, mt * NT + nt, fast_tag, std::false_type{});
+          if (mt & 1) __builtin_amdgcn_sched_barrier(0);
+        }
+        store_rows_lean(ps, nt);
+      }
+      seq += STORE_REQS;
+      return;
+    }
     if (has_res) wait_vm_dyn(seq - mark_r[par]);          // residual rows of this pass
     if (has_res) {
 #pragma unroll
@@ -386,7 +428,7 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
       sh[nt] = all_fast ? s_[nt] - 32 : s_[nt];
       rnd[nt] = all_fast ? 1 << ((s_[nt] - 33) & 31) : 0;
     }
-    if (all_fast && p.relu && !has_act && ps + 1 < P) {
+    if (all_fast && p.relu && !has_act && ps + 1 < P && !g.nopipe) {
       pending = true;
     } else {
       pending = false;
@@ -394,7 +436,7 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
     }
   };
   do_pass(0, 0, std::true_type{});
-  if constexpr (KCH <= 8) {     // (wider inputs stream through the ring once: one pass per workgroup)
+  if constexpr (KCH <= 8 && !LEAN) {     // (wider inputs stream through the ring once: one pass per workgroup)
     for (int ps = 1; ps < P; ps += 2) {
       do_pass(ps, 1, std::false_type{});
       if (ps + 1 < P) do_pass(ps + 1, 0, std::false_type{});

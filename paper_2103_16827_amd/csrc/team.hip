@@ -308,6 +308,7 @@ __device__ __forceinline__ void team_pointwise(int i, const volatile TeamState* 
     g.tiles_per_xcd = g.tiles;
     g.splits = 1;
     g.pps = g.passes;
+    g.nopipe = 0;
     if (vb >= (unsigned)g.tiles) break;
     pwp::pw_pipe_tile<kTeamMT, KCH, false, true, kTeamLook>(p, g, vb, lds, wave * 64 + lane_id());
     __syncthreads();                              // the tile in LDS is free again

@@ -20,6 +20,8 @@ Tuning read_env() {
   t.no_conv_pipe = getenv("QASR_NO_CONV_PIPE") != nullptr;
   t.team = getenv("QASR_TEAM") != nullptr;
   t.cp_plain_order = getenv("QASR_CP_PLAIN_ORDER") != nullptr;
+  t.pw_lean = getenv("QASR_PW_LEAN") != nullptr;
+  t.pwp_nopipe = getenv("QASR_PWP_NOPIPE") != nullptr;
   if (const char* e = getenv("QASR_PWP_MT")) t.pwp_mt = atoi(e);
   if (const char* e = getenv("QASR_PWP_SPLIT")) t.pwp_split = atoi(e);
   if (const char* e = getenv("QASR_DWP")) {
@@ -32,6 +34,10 @@ Tuning read_env() {
     if (sscanf(e, "%d,%d", &mt, &nt) >= 1) { t.cp_mt = mt; t.cp_nt = nt; }
   }
   if (const char* e = getenv("QASR_PWT_MT")) t.pwt_mt = atoi(e);
+  if (const char* e = getenv("QASR_SLOT_DEPTH")) {
+    const int d = atoi(e);
+    if (d >= 0 && d <= 16) t.slot_depth = d;
+  }
   return t;
 }
 

@@ -8,6 +8,10 @@
 //   QASR_CP_TILE = "MT,NT"                  conv_pipe: tile
 //   QASR_CP_PLAIN_ORDER                     conv_pipe: tile = workgroup index (no per-XCD runs of the channel-major order)
 //   QASR_PWT_MT                             pw_tile: groups per tile
+//   QASR_PWP_NOPIPE                         pw_pipe: no epilogue under the next pass's products
+//   QASR_PW_LEAN                            pw_pipe: the lean form (one pass per workgroup, two workgroups per unit)
+//   QASR_SLOT_DEPTH                         encoder: an op's output avoids the buffers the last N ops touched
+//                                           (default 4; 0 = the caller's slots are the buffers)
 //   QASR_TEAM                               encoder: plan runs of layers for the persistent team kernel
 //                                           (experimental, off unless set)
 #pragma once
@@ -15,12 +19,13 @@
 namespace qasr {
 
 struct Tuning {
-  bool no_pw_pipe = false, no_conv_pipe = false, team = false, cp_plain_order = false;
+  bool no_pw_pipe = false, no_conv_pipe = false, team = false, cp_plain_order = false, pw_lean = false, pwp_nopipe = false;
   int pwp_mt = 0, pwp_split = 0;
   int dwp_r = 0, dwp_s = 0;
   int dw_r = 0;
   int cp_mt = 0, cp_nt = 0;
   int pwt_mt = 0;
+  int slot_depth = 4;
 };
 
 const Tuning& tuning();

@@ -331,3 +331,49 @@ def test_the_partial_write_check_follows_includes_and_no_kernel_uses_such_writes
     (tmp_path / "h.hpp").write_text('asm("v_ashrrev_i32_sdwa %0, %1, %2 dst_sel:BYTE_0");\n')
     (tmp_path / "k.hip").write_text('#include "h.hpp"\n__global__ void k() {}\n')
     assert "_sdwa" in source_with_local_includes(str(tmp_path / "k.hip"))
+
+
+def _replay(wiring, in_buf, res_buf, out_buf):
+    """Symbolic replay: every op must find, in the buffer the plan points it to, the value that the
+    caller's slot wiring meant; no op may write a buffer it reads."""
+    slot_val, buf_val = {0: 0}, {0: 0}
+    for i, (si, sr, so) in enumerate(wiring):
+        assert buf_val.get(in_buf[i]) == slot_val[si], f"op {i}: wrong input value"
+        if sr >= 0:
+            assert buf_val.get(res_buf[i]) == slot_val[sr], f"op {i}: wrong residual value"
+        else:
+            assert res_buf[i] == -1
+        assert out_buf[i] not in (in_buf[i], res_buf[i]) and out_buf[i] >= 1
+        slot_val[so] = buf_val[out_buf[i]] = i + 1
+
+
+@pytest.mark.parametrize("depth", [0, 1, 2, 4, 7])
+def test_slot_buffer_plan_keeps_the_dataflow_and_avoids_recently_touched_buffers(depth):
+    """qasr_plan_slot_buffers on the wiring of every benchmark configuration: the dataflow of the
+    slots is kept (symbolic replay), and for depth >= 1 no op writes a buffer that one of the `depth`
+    ops before it read or wrote."""
+    import qasr_workloads as W
+    for cfg in range(7):
+        net = W.build_config(cfg)
+        wiring = [(o.in_slot, o.res_slot, o.out_slot) for o in net.ops if not o.more_res]
+        if len(wiring) != len(net.ops):
+            continue                       # (dense residuals: more operands than this entry point takes)
+        ib, rb, ob, nb = Q.plan_slot_buffers([w[0] for w in wiring], [w[1] for w in wiring], [w[2] for w in wiring],
+                                             net.n_slots, depth)
+        _replay(wiring, ib, rb, ob)
+        if depth == 0:
+            assert (ib, rb, ob) == ([w[0] for w in wiring], [w[1] for w in wiring], [w[2] for w in wiring])
+            continue
+        assert nb <= net.n_slots + depth + 1
+        for i in range(len(wiring)):
+            for j in range(max(0, i - depth), i):
+                assert ob[i] not in (ib[j], rb[j], ob[j]), (cfg, i, j)
+
+
+def test_slot_buffer_plan_rejects_bad_wiring():
+    with pytest.raises(Q.QasrError):
+        Q.plan_slot_buffers([0, 2], [-1, -1], [1, 3], 4, 4)       # slot 2 read before anything wrote it
+    with pytest.raises(Q.QasrError):
+        Q.plan_slot_buffers([0], [-1], [1], 2, 17)
+    with pytest.raises(Q.QasrError):
+        Q.plan_slot_buffers([0, 1], [-1, -1], [1, 1], 2, 1)       # writes the slot it reads
