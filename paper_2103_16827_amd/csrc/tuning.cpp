@@ -20,7 +20,8 @@ Tuning read_env() {
   t.no_conv_pipe = getenv("QASR_NO_CONV_PIPE") != nullptr;
   t.team = getenv("QASR_TEAM") != nullptr;
   t.cp_plain_order = getenv("QASR_CP_PLAIN_ORDER") != nullptr;
-  t.pw_lean = getenv("QASR_PW_LEAN") != nullptr;
+  t.no_pw_lean = getenv("QASR_NO_PW_LEAN") != nullptr;
+  t.pw_lean_force = getenv("QASR_PW_LEAN") != nullptr;
   t.pwp_nopipe = getenv("QASR_PWP_NOPIPE") != nullptr;
   if (const char* e = getenv("QASR_PWP_MT")) t.pwp_mt = atoi(e);
   if (const char* e = getenv("QASR_PWP_SPLIT")) t.pwp_split = atoi(e);

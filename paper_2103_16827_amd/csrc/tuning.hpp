@@ -9,7 +9,8 @@
 //   QASR_CP_PLAIN_ORDER                     conv_pipe: tile = workgroup index (no per-XCD runs of the channel-major order)
 //   QASR_PWT_MT                             pw_tile: groups per tile
 //   QASR_PWP_NOPIPE                         pw_pipe: no epilogue under the next pass's products
-//   QASR_PW_LEAN                            pw_pipe: the lean form (one pass per workgroup, two workgroups per unit)
+//   QASR_PW_LEAN                            pw_pipe: the lean form for every layer it can take, whatever the launch size
+//   QASR_NO_PW_LEAN                         pw_pipe: never the lean form (one pass per workgroup, two workgroups per unit)
 //   QASR_SLOT_DEPTH                         encoder: an op's output avoids the buffers the last N ops touched
 //                                           (default 4; 0 = the caller's slots are the buffers)
 //   QASR_TEAM                               encoder: plan runs of layers for the persistent team kernel
@@ -19,7 +20,7 @@
 namespace qasr {
 
 struct Tuning {
-  bool no_pw_pipe = false, no_conv_pipe = false, team = false, cp_plain_order = false, pw_lean = false, pwp_nopipe = false;
+  bool no_pw_pipe = false, no_conv_pipe = false, team = false, cp_plain_order = false, no_pw_lean = false, pw_lean_force = false, pwp_nopipe = false;
   int pwp_mt = 0, pwp_split = 0;
   int dwp_r = 0, dwp_s = 0;
   int dw_r = 0;

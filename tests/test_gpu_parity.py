@@ -300,6 +300,35 @@ def test_pipelined_pointwise_output_channel_splits(case, split, tuning_env):
     assert run_layer_case((op, p, x, r, packed)) == "pw_pipe"
 
 
+# The lean form of the pointwise kernel (one 256-channel pass per workgroup, two workgroups per
+# compute unit): chosen by launch size in the encoders, forced here on small layers so that every
+# epilogue variant, a ragged last tile and padded output strides go through it.
+LEAN = [
+    dict(name="lean_512_512_ragged_tiles", B=3, Cin=512, Cout=512, T=336, packed=True),
+    dict(name="lean_256_1024_norelu", B=2, Cin=256, Cout=1024, T=160, relu=False, packed=True),
+    dict(name="lean_512_768_nobias_generic_s", B=1, Cin=512, Cout=768, T=208, bias=False, s_lo=20, s_hi=40, packed=True),
+    dict(name="lean_256_256_s33", B=2, Cin=256, Cout=256, T=160, s_lo=33, s_hi=33, packed=True),
+    dict(name="lean_512_2048_minus128", B=1, Cin=512, Cout=2048, T=400, wmin=-128, packed=True),
+    dict(name="lean_256_512_s_50_to_60", B=2, Cin=256, Cout=512, T=112, s_lo=50, s_hi=60, packed=True),
+]
+
+
+@pytest.mark.parametrize("extra", [0, 16])
+@pytest.mark.parametrize("kw", LEAN, ids=[c["name"] for c in LEAN])
+def test_lean_pointwise_layers(kw, extra, tuning_env):
+    tuning_env("QASR_PW_LEAN", "1")
+    assert run_layer_case(layer_case(**kw), extra) == "pw_pipe"
+
+
+def test_lean_pointwise_is_what_large_launches_take_and_can_be_switched_off(tuning_env):
+    """A layer with enough workgroups to share the units (the size at which the encoders use the
+    lean form), then the same layer with the form switched off: same bytes."""
+    case = layer_case(name="lean_by_size", B=8, Cin=256, Cout=1024, T=800, packed=True)
+    assert run_layer_case(case) == "pw_pipe"
+    tuning_env("QASR_NO_PW_LEAN", "1")
+    assert run_layer_case(case) == "pw_pipe"
+
+
 @pytest.mark.parametrize("slow_passes", [(1,), (0,), (1, 2), (0, 3)])
 def test_pipelined_pointwise_mixed_rescale_forms(slow_passes):
     """Passes whose s values are all >= 33 are pipelined, the others take the 64-bit form right
