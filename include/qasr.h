@@ -275,7 +275,8 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
  * longer; the two-slot ping-pong of a plain layer chain does that in every layer (measured: the
  * QuartzNet-15x5 shape at batch 32 takes 1.77 ms per forward with the slots as buffers, 1.49 ms
  * with depth 4).  Depth 0 keeps the caller's slots as the buffers.  The workspace grows by up to
- * `depth` buffers.
+ * `depth` buffers; the depth is lowered until the buffers together take at most 192 MiB (they
+ * should stay in the 256 MB memory-side cache together), down to 0.
  *   qasr_plan_slot_buffers: the same plan on bare wiring (HOST only, no device needed; for tests and
  *   diagnostics): in/res/out_slot[n_ops] as in qasr_op (res -1 for none) -> in/res/out_buf[n_ops]
  *   (buffer 0 is the network input) and the number of buffers; QASR_ERR_PARAM for wiring that

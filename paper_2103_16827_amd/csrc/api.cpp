@@ -656,7 +656,18 @@ qasr_status qasr_encoder_create(const qasr_op* ops, int32_t n_ops, int32_t n_slo
                           i + 1 == n_ops ? (size_t)0   // (the last op writes the caller's output)
                                          : (size_t)o.d.B * o.d.Cout * (size_t)out_len64(&o.d)};
     }
-    plan_slots(wires, n_slots, qasr::tuning().slot_depth, plan);
+    // The buffers should stay inside the 256 MB memory-side cache together: the deepest plan up to
+    // the configured depth whose buffers take at most three quarters of it (QuartzNet-15x5 shape:
+    // depth 4 at batch 32, 118 MB; depth 2 at batch 64, 2.44 against 2.46 ms with depth 4 and 2.60
+    // with the slots as buffers; at batch 128 even those take 264 MB and every further buffer
+    // costs: 4.78 ms with depth 0, 4.92 with 1, 5.53 with 4).
+    const size_t budget = (size_t)192 << 20;
+    for (int depth = qasr::tuning().slot_depth; depth >= 0; --depth) {
+      plan_slots(wires, n_slots, depth, plan);
+      size_t total = 0;
+      for (size_t b = 1; b < plan.bytes.size(); ++b) total += round256(plan.bytes[b]);
+      if (total <= budget) break;
+    }
   }
   const int32_t n_bufs = (int32_t)plan.bytes.size();
   e->slot_off.assign(n_bufs, 0);
