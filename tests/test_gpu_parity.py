@@ -504,6 +504,31 @@ def test_forward_is_deterministic_and_leaves_guard_bytes():
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
 
 
+@pytest.mark.parametrize("depth", ["0", "1", "7"])
+def test_buffer_plan_depths_give_the_same_bytes(depth, tuning_env):
+    """The library decides which workspace buffer a slot's value lives in (no op writes a buffer
+    that recent ops touched); whatever the depth of that plan, the caller's slots themselves
+    included, the outputs are the same bytes, and the workspace grows with the depth."""
+    net = W.quartznet(4, 640, 1, config_id=1)
+    params = W.draw_net_params(net, 4)
+    x = dev(W.draw_input(net, 4))
+    g0 = GpuNet(net, params)                       # the default plan
+    want = g0.forward(x).clone()
+    g0.check_guards()
+    tuning_env("QASR_SLOT_DEPTH", depth)
+    g = GpuNet(net, params)
+    got = g.forward(x)
+    g.check_guards()
+    assert torch.equal(got, want)
+    if depth == "0":
+        assert g.enc.workspace_bytes < g0.enc.workspace_bytes
+    if depth == "7":
+        assert g.enc.workspace_bytes > g0.enc.workspace_bytes
+    ref = oracle.encoder_forward(W.NetSpec(net.name, net.config_id, 1, net.Cin, net.Tin, net.ops, net.n_slots), params,
+                                 np.ascontiguousarray(W.draw_input(net, 4)[1:2]))
+    assert np.array_equal(got[1:2].cpu().numpy(), ref)
+
+
 def test_workspace_errors():
     net = W.tiny_config(1)
     params = W.draw_net_params(net, 1)
