@@ -107,15 +107,16 @@ bool pick(const ConvParams& p, Choice& c, int cus) {
   if (passes & (passes - 1)) {                              // (splits run over powers of two)
     if (c.KCH > 8) return false;
   }
-  // The lean form (every pass a workgroup of its own, two workgroups per unit) for plain layers whose
-  // tile stays resident, when all its workgroups are resident at once: 7 groups per tile.  Single
+  // The lean form (every pass a workgroup of its own, two workgroups per unit) for layers without a
+  // fused activation whose tile stays resident, when all its workgroups are resident at once: 7 groups per tile.  Single
   // layers at B=32, T=800 against the form above: 256->256 13.0 against 14.0 us, 256->512 14.9
   // against 17.5, 512->512 13.8 against 15.4, 512->1024 (two rounds) no difference; smaller tiles
   // are slower (more workgroups than resident slots, or the weights streamed more often).  Launches
   // that leave most units empty keep the pipelined form (batch 1: 0.313 against 0.330 ms for the
   // QuartzNet-5x5 shape).
   const int64_t lean_wgs = ((G + kMaxMT - 1) / kMaxMT) * passes;
-  c.lean = !tuning().no_pw_lean && !p.res && !p.act_lut && c.KCH <= 8 && p.Cout % (8 * ROWS) == 0 &&
+  c.lean = !tuning().no_pw_lean && !(p.res && tuning().pw_lean_no_res) && !p.act_lut && c.KCH <= 8 &&
+           p.Cout % (8 * ROWS) == 0 &&
            (tuning().pw_lean_force || (2 * lean_wgs > cus && lean_wgs <= 2 * (int64_t)cus));
   if (c.lean) { c.splits = passes; c.MT = kMaxMT; }
   {                                                       // tuning overrides

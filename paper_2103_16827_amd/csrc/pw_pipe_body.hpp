@@ -49,8 +49,12 @@ constexpr int lds_bytes_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 2 * ROWS *
 // The lean form (see LEAN below): the activation tile and one 16-row staging block per wave, which
 // also holds the wave's constants until the epilogue starts; at 512 input channels exactly half
 // of a compute unit's LDS, so that two workgroups are resident together.
+// Residual rows (4 KiB per wave) have an area of their own after the staging blocks at 256 input
+// channels; at 512 there is no room left, and they land in the LDS of the first four activation
+// chunks once every wave is done with those (see the chunk loop).
 template <int KCH>
-constexpr int lds_bytes_lean_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 16 * 128; }
+constexpr int lds_bytes_lean_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 16 * 128 + (KCH < 8 ? 8 * 4096 : 0); }
+constexpr int kLeanResAfter = 5;   // 512 input channels: residual rows requested behind the barrier of chunk step 5
 
 // ACT: a unary activation's table is applied after the clamp (an instantiation of its own: the
 // plain layers keep their code as it is)
@@ -60,7 +64,7 @@ constexpr int lds_bytes_lean_c() { return (KCH < 8 ? KCH : 8) * 8192 + 8 * 16 * 
 // the XCD's L2), and the output rows are stored write-back (the next layer reads them from that L2).
 // LOOK: weight chunks requested ahead of the one being multiplied (a ring of LOOK x NT x 4 registers).
 // LEAN: exactly one pass per workgroup (the launcher gives every pass of a tile a workgroup of its
-// own), one accumulator set, no residual operand, no fused activation, staging of 16 rows at a
+// own), one accumulator set, no fused activation, staging of 16 rows at a
 // time: half the registers and half the LDS, so that two workgroups share a compute unit and each
 // SIMD has four waves to pick instructions from; the epilogue of one workgroup then overlaps the
 // products of the other by chance instead of by construction.
@@ -107,7 +111,9 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
   // (lean: the constants of the one pass sit in the wave's staging block, 384 of its 2048 bytes, and
   // are all in registers before the first staged word is written)
   unsigned char* const cst0 = LEAN ? stage0 : xs + XCH * 8192 + 8 * 2 * ROWS * 128 + wave * (MAXP * NT * 3 * 64);
-  const bool has_res = !LEAN && p.res != nullptr;
+  const bool has_res = p.res != nullptr;
+  // (lean: where the wave's residual rows land, [NT][16 rows][128 B])
+  unsigned char* const lres0 = KCH < 8 ? xs + XCH * 8192 + 8 * 16 * 128 + wave * 4096 : xs + wave * 4096;
   unsigned char* const lutw = xs + XCH * 8192 + 8 * 2 * ROWS * 128 + 8 * (MAXP * NT * 3 * 64) + wave * 256;
   constexpr bool has_act = ACT;                     // a unary activation follows the clamp
 
@@ -117,11 +123,12 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
   auto issue_residual = [&](int ps, int par) __attribute__((always_inline)) {   // residual rows of pass ps -> stage[par]
     if (has_res) {
       const int co_w = ((pb + ps) * 8 + wave) * ROWS;
+      unsigned char* const dst = LEAN ? lres0 : stage0 + par * (ROWS * 128);
 #pragma unroll
       for (int it = 0; it < 2 * NT; ++it) {
         const int co = co_w + 8 * it + (lane >> 3);
         if (u_ok && co < p.Cout)
-          direct_load16_scope<TEAM>(p.res + yoff_l + (int64_t)co * p.Tout, stage0 + par * (ROWS * 128) + it * 1024);
+          direct_load16_scope<TEAM>(p.res + yoff_l + (int64_t)co * p.Tout, dst + it * 1024);
         if (co_w + 8 * it < p.Cout) ++seq;       // issued iff some lane had a row (lane 0 has unit 0)
       }
     }
@@ -149,7 +156,7 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
 
   // ---- requests of the start: residual of pass 0, constants of all passes, then the first weight
   // and activation chunks (the first products need only 64 channels)
-  issue_residual(0, 0);
+  if (!LEAN || KCH < 8) issue_residual(0, 0);
   for (int ps = 0; ps < P; ++ps) {
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -203,7 +210,7 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
     constexpr bool FAST = decltype(fast_tag)::value, RES = decltype(res_tag)::value;
     const int mt = e / NT, nt = e % NT;
     uint32_t* const sp = reinterpret_cast<uint32_t*>(stage0 + (LEAN ? 0 : par * (ROWS * 128) + nt * 2048) + (sbase ^ (uint32_t)(mt << 4)));
-    const uint32_t rw = RES ? *sp : 0u;
+    const uint32_t rw = !RES ? 0u : LEAN ? *reinterpret_cast<const uint32_t*>(lres0 + nt * 2048 + (sbase ^ (uint32_t)(mt << 4))) : *sp;
     const v4i av = acc[par][mt][nt];
     const int32_t a4[4] = {av[0], av[1], av[2], av[3]};
     uint32_t pk = requant_pack4<FAST, RES>(a4, mc[nt], sh[nt], rnd[nt], rw, lo, hi127);
@@ -287,12 +294,21 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
   // the epilogue of pass ps on its own
   auto epilogue_alone = [&](int ps, int par, auto fast_tag) __attribute__((always_inline)) {
     if constexpr (LEAN) {
+      if (has_res) wait_vm_dyn(seq - mark_r[0]);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
+        if (has_res) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          block(par, mt * NT + nt, fast_tag, std::false_type{});
-          if (mt & 1) __builtin_amdgcn_sched_barrier(0);
+          for (int mt = 0; mt < MT; ++mt) {
+            block(par, mt * NT + nt, fast_tag, std::true_type{});
+            if (mt & 1) __builtin_amdgcn_sched_barrier(0);
+          }
+        } else {
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            block(par, mt * NT + nt, fast_tag, std::false_type{});
+            if (mt & 1) __builtin_amdgcn_sched_barrier(0);
+          }
         }
         store_rows_lean(ps, nt);
       }
@@ -362,6 +378,9 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
       if (FIRST) {
         __syncthreads();                          // publishes the other waves' rows of the chunk
         if (kk + LOOKX < KCH) issue_x(kk + LOOKX);
+        // lean, 512 input channels: behind this barrier every wave has read the chunks before
+        // kk - 1 for the last time, so from step 5 on the LDS of chunks 0..3 can take the residual rows
+        if (LEAN && KCH == 8 && kk == kLeanResAfter) issue_residual(0, 0);
       }
       {
         const unsigned char* ab = xs + (kk & 7) * 8192;

@@ -22,6 +22,7 @@ Tuning read_env() {
   t.cp_plain_order = getenv("QASR_CP_PLAIN_ORDER") != nullptr;
   t.no_pw_lean = getenv("QASR_NO_PW_LEAN") != nullptr;
   t.pw_lean_force = getenv("QASR_PW_LEAN") != nullptr;
+  t.pw_lean_no_res = getenv("QASR_PW_LEAN_NO_RES") != nullptr;
   t.pwp_nopipe = getenv("QASR_PWP_NOPIPE") != nullptr;
   if (const char* e = getenv("QASR_PWP_MT")) t.pwp_mt = atoi(e);
   if (const char* e = getenv("QASR_PWP_SPLIT")) t.pwp_split = atoi(e);

@@ -10,6 +10,7 @@
 //   QASR_PWT_MT                             pw_tile: groups per tile
 //   QASR_PWP_NOPIPE                         pw_pipe: no epilogue under the next pass's products
 //   QASR_PW_LEAN                            pw_pipe: the lean form for every layer it can take, whatever the launch size
+//   QASR_PW_LEAN_NO_RES                     pw_pipe: layers with a residual operand keep the pipelined form
 //   QASR_NO_PW_LEAN                         pw_pipe: never the lean form (one pass per workgroup, two workgroups per unit)
 //   QASR_SLOT_DEPTH                         encoder: an op's output avoids the buffers the last N ops touched
 //                                           (default 4; 0 = the caller's slots are the buffers)
@@ -20,7 +21,7 @@
 namespace qasr {
 
 struct Tuning {
-  bool no_pw_pipe = false, no_conv_pipe = false, team = false, cp_plain_order = false, no_pw_lean = false, pw_lean_force = false, pwp_nopipe = false;
+  bool no_pw_pipe = false, no_conv_pipe = false, team = false, cp_plain_order = false, no_pw_lean = false, pw_lean_force = false, pw_lean_no_res = false, pwp_nopipe = false;
   int pwp_mt = 0, pwp_split = 0;
   int dwp_r = 0, dwp_s = 0;
   int dw_r = 0;

@@ -310,6 +310,12 @@ LEAN = [
     dict(name="lean_256_256_s33", B=2, Cin=256, Cout=256, T=160, s_lo=33, s_hi=33, packed=True),
     dict(name="lean_512_2048_minus128", B=1, Cin=512, Cout=2048, T=400, wmin=-128, packed=True),
     dict(name="lean_256_512_s_50_to_60", B=2, Cin=256, Cout=512, T=112, s_lo=50, s_hi=60, packed=True),
+    # with a residual operand: its rows land in an LDS area of their own (256 input channels) or in the
+    # LDS of activation chunks the products are done with (512)
+    dict(name="lean_512_512_res_ragged_tiles", B=3, Cin=512, Cout=512, T=336, res=True, packed=True),
+    dict(name="lean_512_1024_res_generic_s", B=2, Cin=512, Cout=1024, T=208, res=True, s_lo=20, s_hi=40, packed=True),
+    dict(name="lean_256_256_res_norelu", B=2, Cin=256, Cout=256, T=160, res=True, relu=False, packed=True),
+    dict(name="lean_256_768_res_s33", B=1, Cin=256, Cout=768, T=480, res=True, s_lo=33, s_hi=33, packed=True),
 ]
 
 
