@@ -80,7 +80,7 @@ __device__ __forceinline__ void pw_pipe_tile(const ConvParams& p, const PwpGeom&
   // (inside the team kernel's layer loop: keeps everything derived from the thread id inside the
   // tile, or the compiler computes the lane constants of every layer body once, ahead of the loop,
   // and has to carry them through all the bodies in registers that do not exist)
-  if (TEAM) asm volatile("" : "+v"(tid));
+  if constexpr (TEAM) asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, gi = lane >> 4;
