@@ -24,6 +24,8 @@
 
 using namespace qasr;
 using namespace qasr::pwp;
+using sim::Wave;
+using sim::merge;
 
 namespace {
 
@@ -34,59 +36,6 @@ struct Case {
   int res, relu, bias, splits;
   int slow_pass;           // a pass whose s is below 33 (unpipelined 64-bit epilogue), -1 for none
 };
-
-struct Wave { std::vector<std::vector<sim::Ev>> lanes; };
-
-bool same(const sim::Ev& a, const sim::Ev& b) { return a.k == b.k && a.a == b.a && a.b == b.b; }
-
-// merge the 64 lane streams: events are equal across lanes except that a lane may skip a
-// direct-to-LDS load (masked out) that others issue
-std::vector<sim::Ev> merge(const Wave& w) {
-  std::vector<size_t> pos(64, 0);
-  std::vector<sim::Ev> out;
-  for (;;) {
-    int done = 0;
-    for (int l = 0; l < 64; ++l) done += pos[l] == w.lanes[l].size();
-    if (done == 64) break;
-    // candidate: a masked load that some lane has next, else the common next event
-    const sim::Ev* cand = nullptr;
-    bool all_equal = true;
-    const sim::Ev* first = nullptr;
-    for (int l = 0; l < 64; ++l) {
-      if (pos[l] == w.lanes[l].size()) { all_equal = false; continue; }
-      const sim::Ev& e = w.lanes[l][pos[l]];
-      if (!first) first = &e;
-      else if (!same(e, *first)) all_equal = false;
-    }
-    if (all_equal && done == 0) {
-      cand = first;
-    } else {
-      // the earliest-in-program-order differing event is a masked load: pick an ISSUE_LDS some lane has
-      for (int l = 0; l < 64 && !cand; ++l)
-        if (pos[l] < w.lanes[l].size() && w.lanes[l][pos[l]].k == sim::ISSUE_LDS) {
-          // it must not be the next event of every lane (handled above) and lanes that lack it must be
-          // at a later event
-          cand = &w.lanes[l][pos[l]];
-        }
-      if (!cand) {
-        std::string d;
-        for (int l = 0; l < 64; l += 9)
-          if (pos[l] < w.lanes[l].size())
-            d += " lane " + std::to_string(l) + ": kind " + std::to_string(w.lanes[l][pos[l]].k) + " a " +
-                 std::to_string(w.lanes[l][pos[l]].a) + " b " + std::to_string(w.lanes[l][pos[l]].b) + ";";
-        sim::fail("the lanes of a wave disagree on something other than a masked load (event " +
-                  std::to_string(out.size()) + ":" + d + ")");
-      }
-    }
-    const sim::Ev c = *cand;
-    out.push_back(c);
-    int advanced = 0;
-    for (int l = 0; l < 64; ++l)
-      if (pos[l] < w.lanes[l].size() && same(w.lanes[l][pos[l]], c)) { ++pos[l]; ++advanced; }
-    if (c.k != sim::ISSUE_LDS && advanced != 64) sim::fail("a wave-uniform event is missing in some lanes");
-  }
-  return out;
-}
 
 struct Req { sim::Kind k; int64_t a, b; bool done; };
 

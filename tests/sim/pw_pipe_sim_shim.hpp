@@ -18,6 +18,11 @@
 #define __forceinline__ inline
 #define __global__
 #define __restrict__
+#define __launch_bounds__(...)
+#define __shared__ static
+#define __align__(n) __attribute__((aligned(n)))
+struct SimDim3 { unsigned x = 0, y = 0, z = 0; };
+inline SimDim3 threadIdx, blockIdx;
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -44,6 +49,11 @@ struct State {
   // dword loads into LDS (the per-channel constants) of the whole wave: the lanes run one after the
   // other here, so what the other lanes of the wave load is put in place before each lane runs
   std::vector<std::pair<size_t, uint32_t>> dwords;
+  // wave-wide ballots: the first round over a wave's lanes collects them, the second returns them
+  std::vector<uint64_t> ballots;
+  size_t ballot_idx = 0;
+  bool second_round = false;
+  std::vector<int32_t> reg_values;       // value behind each register-load tag (index = uid)
 };
 inline State& S() { static State s; return s; }
 
@@ -67,6 +77,66 @@ inline size_t lds_off(const void* p, size_t n) {
   if (q < S().lds || q + n > S().lds + S().lds_bytes) fail("LDS address outside the workgroup's allocation");
   return (size_t)(q - S().lds);
 }
+
+// ---- the 64 lane records of a wave, merged into the wave's instruction stream
+struct Wave { std::vector<std::vector<Ev>> lanes; };
+
+// (the lanes of a wave read different bytes of the same LDS rows: a use is compared by kind only)
+// what only some lanes of a wave may take part in: a load under a lane predicate, and the use of its register
+inline bool maskable(Kind k) { return k == ISSUE_LDS || k == ISSUE_REG || k == USE_REG; }
+inline bool same(const Ev& a, const Ev& b) { return a.k == b.k && (a.k == USE_LDS || (a.a == b.a && a.b == b.b)); }
+
+// merge the 64 lane streams: events are equal across lanes except that a lane may skip a
+// load (masked out) that others issue
+inline std::vector<Ev> merge(const Wave& w) {
+  std::vector<size_t> pos(64, 0);
+  std::vector<Ev> out;
+  for (;;) {
+    int done = 0;
+    for (int l = 0; l < 64; ++l) done += pos[l] == w.lanes[l].size();
+    if (done == 64) break;
+    // candidate: a masked load that some lane has next, else the common next event
+    const Ev* cand = nullptr;
+    bool all_equal = true;
+    const Ev* first = nullptr;
+    for (int l = 0; l < 64; ++l) {
+      if (pos[l] == w.lanes[l].size()) { all_equal = false; continue; }
+      const Ev& e = w.lanes[l][pos[l]];
+      if (!first) first = &e;
+      else if (!same(e, *first)) all_equal = false;
+    }
+    if (all_equal && done == 0) {
+      cand = first;
+    } else {
+      // the earliest-in-program-order differing event is a masked load: pick an ISSUE_LDS some lane has
+      for (int l = 0; l < 64 && !cand; ++l)
+        if (pos[l] < w.lanes[l].size() && maskable(w.lanes[l][pos[l]].k)) {
+          // it must not be the next event of every lane (handled above) and lanes that lack it must be
+          // at a later event
+          cand = &w.lanes[l][pos[l]];
+        }
+      if (!cand) {
+        std::string d;
+        for (int l = 0; l < 64; l += 9)
+          if (pos[l] < w.lanes[l].size())
+            d += " lane " + std::to_string(l) + ": kind " + std::to_string(w.lanes[l][pos[l]].k) + " a " +
+                 std::to_string(w.lanes[l][pos[l]].a) + " b " + std::to_string(w.lanes[l][pos[l]].b) + ";";
+        fail("the lanes of a wave disagree on something other than a masked load (event " +
+                  std::to_string(out.size()) + ":" + d + ")");
+      }
+    }
+    const Ev c = *cand;
+    out.push_back(c);
+    int advanced = 0, top = -1;
+    for (int l = 0; l < 64; ++l)
+      if (pos[l] < w.lanes[l].size() && same(w.lanes[l][pos[l]], c)) { ++pos[l]; ++advanced; top = l; }
+    // a load into LDS reaches as far as its highest participating lane (recorded: 64 lanes' worth)
+    if (c.k == ISSUE_LDS) out.back().b = c.b / 64 * (top + 1);
+    if (!maskable(c.k) && advanced != 64) fail("a wave-uniform event is missing in some lanes");
+  }
+  return out;
+}
+
 
 }  // namespace sim
 
@@ -98,7 +168,8 @@ inline uint32_t requant_pack4(const int32_t (&a)[4], int32_t m, int32_t sh, int3
 // ---- what vmem.hpp gives the tile
 inline void direct_load_n(const void* gptr, const unsigned char* lds_wave_base, int n) {
   sim::region_of(gptr, n, false);
-  const size_t off = sim::lds_off(lds_wave_base, 64 * (size_t)n);
+  // (the bytes of this lane must be inside the allocation; lanes that stay out of a load write nothing)
+  const size_t off = sim::lds_off(lds_wave_base + (size_t)n * sim::S().lane, n) - (size_t)n * sim::S().lane;
   std::memcpy(sim::S().lds + off + (size_t)n * sim::S().lane, gptr, n);      // (data as if it had landed at once)
   if (n == 4) {
     uint32_t v;
@@ -136,7 +207,28 @@ inline void tie(v4i& v) {
     sim::rec(sim::USE_REG, (int64_t)((uint32_t)v.x & 0x00ffffffu));
   }
 }
-inline void tie(int32_t&) {}
+// one dword / one sign-extended byte into a register: the tag stands for the value until the tie
+inline int32_t reg_load(const void* p, int bytes) {
+  sim::region_of(p, bytes, false);
+  int32_t v = 0;
+  if (bytes == 4) std::memcpy(&v, p, 4);
+  else v = *(const int8_t*)p;
+  auto& st = sim::S();
+  const int uid = st.next_uid++;
+  if ((size_t)uid >= st.reg_values.size()) st.reg_values.resize(uid + 1);
+  st.reg_values[uid] = v;
+  sim::rec(sim::ISSUE_REG, uid);
+  return (int32_t)(kUidTag | (uint32_t)uid);
+}
+inline int32_t gload4(const void* p) { return reg_load(p, 4); }
+inline int32_t gload_i8(const void* p) { return reg_load(p, 1); }
+inline void tie(int32_t& v) {
+  if (((uint32_t)v & 0xff000000u) == kUidTag) {
+    const int uid = (int)((uint32_t)v & 0x00ffffffu);
+    sim::rec(sim::USE_REG, uid);
+    v = sim::S().reg_values[uid];
+  }
+}
 
 }  // namespace qasr
 
@@ -156,6 +248,33 @@ inline void sim_buffer_store16(V, SimRsrc r, uint32_t off, int, int) {
     for (int i = 0; i < 16; ++i) ++(*st.written)[o + i];
 }
 #define __builtin_amdgcn_raw_buffer_store_b128(v, r, off, soff, aux) sim_buffer_store16(v, r, off, soff, aux)
+inline void sim_buffer_store4(uint32_t, SimRsrc r, uint32_t off, int, int) {
+  sim::rec(sim::STORE);
+  if ((uint64_t)off + 4 > r.num) return;
+  sim::region_of(r.p + off, 4, true);
+  auto& st = sim::S();
+  const size_t o = (size_t)(r.p + off - st.y_base);
+  if (st.count_stores)
+    for (int i = 0; i < 4; ++i) ++(*st.written)[o + i];
+}
+#define __builtin_amdgcn_raw_buffer_store_b32(v, r, off, soff, aux) sim_buffer_store4(v, r, off, soff, aux)
+inline uint64_t __ballot(bool pred) {
+  auto& st = sim::S();
+  const size_t i = st.ballot_idx++;
+  if (!st.second_round) {
+    if (i >= st.ballots.size()) st.ballots.resize(i + 1, 0);
+    st.ballots[i] |= (uint64_t)pred << st.lane;
+    return (uint64_t)pred << st.lane;
+  }
+  if (i >= st.ballots.size()) sim::fail("a ballot the first round did not see");
+  return st.ballots[i];
+}
+// a plain 16-byte LDS read of loaded rows (the generator of the depthwise replay routes the one such
+// read of that kernel here)
+inline v4i sim_lds_read16(const void* p) {
+  sim::rec(sim::USE_LDS, (int64_t)sim::lds_off(p, 16));
+  return (v4i){0, 0, 0, 0};
+}
 inline int sim_uniform(int x) { sim::rec(sim::UNIFORM, x); return x; }
 inline unsigned sim_uniform(unsigned x) { sim::rec(sim::UNIFORM, (int64_t)x); return x; }
 #define __builtin_amdgcn_readfirstlane(x) sim_uniform(x)
