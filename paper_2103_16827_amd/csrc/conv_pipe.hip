@@ -267,8 +267,13 @@ int lds_rows(const ConvParams& p, int TM) {
 // weight request, loop), and the operand reads of all waves share the unit's LDS port.
 double step_cycles(int MT, int NT, int64_t blocks) {
   const int occ = NT == 4 ? 2 : MT > 4 ? 3 : 4;           // bound by registers
-  const double M = 16.0 * MT * NT, alone = M + 150.0, lds = 32.0 * MT;
-  auto T = [&](int64_t w) { return w == 0 ? 0.0 : fmax(fmax((double)w * M, alone), (double)w * lds); };
+  // (a fourth bound: every wave streams its own NT KiB of weights per step out of L2; fitted, with
+  // the lone wave's latency, to per-layer times of the Jasper shape under every forced tile: only
+  // the widest layer, 768 -> 896 with k = 29, changes its tile, 250 -> 221 us)
+  const double M = 16.0 * MT * NT, alone = M + 250.0, lds = 32.0 * MT, wstream = 80.0 * NT;
+  auto T = [&](int64_t w) {
+    return w == 0 ? 0.0 : fmax(fmax(fmax((double)w * M, alone), (double)w * lds), (double)w * wstream);
+  };
   const int64_t n = (blocks + 255) / 256;                 // workgroups on the busiest unit
   return (double)(n / occ) * T(occ) + T(n % occ);
 }
